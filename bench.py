@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the KSA hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input resident in HBM:
+  prefill of the 128K workload (batch 1, 32/8 heads, head_dim 128, 131072 text tokens, chunks of 64 with
+  8 summary tokens each) followed by one decode step of the 128K-context workload (batch 64, 16376 visible
+  summary rows + 128 text rows per KV head).  The layout / tile schedule depends on shapes only and is built
+  once before the timed region (its build time is reported separately).
+
+Prints one JSON line.  `value` is the prefill throughput in live TFLOP/s (4*d FLOPs per visible (q, k)
+pair, nothing else counted); the decode bandwidth, both rooflines and the CPU oracle baseline ride along.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+
+
+def live_pairs(n, c, m, C):
+    """Visible (query, key) pairs per head of the KSA mask (closed form from Eq. 1 / Eq. 3)."""
+    J = n // c
+    text = sum(min(j, C) * c * c + c * (c + 1) // 2 + max(0, j - C) * m * c for j in range(J))
+    return text + J * (m * c + m * (m + 1) // 2)
+
+
+def time_events(fn, steps):
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    return [e0.elapsed_time(e1) for e0, e1 in evs]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-splits", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2604_24432_amd as K
+    from paper_2604_24432_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    # ---- prefill 128K -----------------------------------------------------------------------------
+    cfg = synth.CONFIGS["prefill_128k"]
+    t0 = time.perf_counter()
+    p = K.make_params(cfg.batch, cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks, cfg.n_q_heads,
+                      cfg.n_kv_heads, cfg.head_dim)
+    lay = K.ksa_build_layout(p)
+    lay.upload()
+    layout_ms = (time.perf_counter() - t0) * 1e3
+    q, k, v = synth.make_prefill_inputs(cfg, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty((cfg.batch, cfg.n_q_heads, cfg.aug_len), dtype=torch.float32, device="cuda")
+
+    # ---- decode on a 128K context --------------------------------------------------------------------
+    dcfg = synth.CONFIGS["decode_128k"]
+    pos = dcfg.decode_pos
+    n_cap = (pos // dcfg.chunk_len + 1) * dcfg.chunk_len
+    dp = K.make_params(dcfg.batch, n_cap, dcfg.chunk_len, dcfg.n_summary, dcfg.window_chunks, dcfg.n_q_heads,
+                       dcfg.n_kv_heads, dcfg.head_dim)
+    s_cap, rows = K.cache_geometry(dp)
+    W = (dcfg.window_chunks + 1) * dcfg.chunk_len
+    base = (pos // dcfg.chunk_len - dcfg.window_chunks) * dcfg.chunk_len
+    dq, k_sum, v_sum, k_txt, v_txt = synth.make_decode_inputs(dcfg, s_cap, W, device="cuda")
+    k_cache, v_cache = K.pack_cache(dp, k_sum, v_sum, k_txt, v_txt, base)
+    del k_sum, v_sum
+    pos_t = torch.full((dcfg.batch,), pos, dtype=torch.int32, device="cuda")
+    do = torch.empty_like(dq)
+    dlse = torch.empty((dcfg.batch, dcfg.n_q_heads), dtype=torch.float32, device="cuda")
+    ws = torch.empty(K.decode_workspace_bytes(dp, args.decode_splits), dtype=torch.uint8, device="cuda")
+    rg = K.ksa_decode_ranges(dp, pos)
+    vis_rows = int(rg[1] + rg[3] + rg[5])
+
+    def prefill():
+        K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse)
+
+    def decode():
+        K.ksa_decode_fwd(dp, dq, k_cache, v_cache, pos_t, o=do, lse=dlse, workspace=ws, n_splits=args.decode_splits)
+
+    def step():
+        prefill()
+        decode()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations with events on the launch stream, over the same number of steps
+    pre_ms = time_events(prefill, args.steps)
+    dec_ms = time_events(decode, args.steps)
+    pre_avg, dec_avg = float(np.mean(pre_ms)), float(np.mean(dec_ms))
+
+    live = live_pairs(cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks)
+    live_flops = 4.0 * cfg.head_dim * cfg.batch * cfg.n_q_heads * live
+    pre_tflops = live_flops / (pre_avg * 1e-3) / 1e12
+    dec_bytes = 2.0 * dcfg.batch * dcfg.n_kv_heads * vis_rows * dcfg.head_dim * 2 \
+        + 2.0 * dcfg.batch * dcfg.n_q_heads * dcfg.head_dim * 2
+    dec_gbs = dec_bytes / (dec_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": "KSA prefill live-TFLOP/s + %MFMA peak @128K; decode HBM GB/s + %peak",
+        "value": round(pre_tflops, 2),
+        "unit": "TFLOP/s (live bf16 FLOPs, 128K prefill)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "prefill_128k (B1 Hq32 Hkv8 d128 n131072 c64 m8 C1, L=147456) + decode_128k "
+                               "(B64 Hq32 Hkv8 d128 pos 131135: 16376 summary + 128 text rows per KV head)",
+                   "layout_build_ms": round(layout_ms, 2), "build": K.build_info()},
+        "prefill": {"ms": round(pre_avg, 4), "ms_min": round(float(np.min(pre_ms)), 4), "live_flops": live_flops,
+                    "live_tflops": round(pre_tflops, 2), "frac_mfma_peak": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "decode": {"ms": round(dec_avg, 5), "ms_min": round(float(np.min(dec_ms)), 5), "bytes": dec_bytes,
+                   "gbs": round(dec_gbs, 1), "frac_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4),
+                   "visible_rows_per_kv_head": vis_rows},
+        "roofline": {"bound": "mfma", "kernel": "ksa_prefill_kernel<128>", "achieved": round(pre_tflops, 2),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+        "roofline_decode": {"bound": "hbm", "kernel": "ksa_decode_split_kernel<128,4>", "achieved": round(dec_gbs, 1),
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
+                            "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, q, k, v, o_gpu, flops_per_pair_all_heads):
+    """The oracle as it stands, on the host cores, over a bounded sample of the same prefill workload:
+    a seeded set of query rows for all heads.  Also checks the GPU output on those rows."""
+    import torch
+    from oracle import ksa_oracle as O
+    gen = np.random.default_rng(12345)
+    rows = np.sort(gen.choice(cfg.aug_len, size=192, replace=False)).astype(np.int64)
+    qf, kf, vf = (x.float().cpu().numpy() for x in (q, k, v))
+    t0 = time.perf_counter()
+    o_ref, _ = O.prefill(qf, kf, vf, cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks, rows=rows)
+    secs = time.perf_counter() - t0
+    pairs = 0
+    for a in rows:
+        pairs += int(O.mask_row(int(a), cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks).sum())
+    flops = flops_per_pair_all_heads * pairs
+    err = np.abs(o_gpu[:, torch.from_numpy(rows).cuda()].float().cpu().numpy() - o_ref)
+    cores = O.num_threads()
+    return {"value": round(flops / secs / 1e12, 6), "unit": "TFLOP/s (live, fp64 oracle)", "cores": cores,
+            "kind": "oracle", "seconds": round(secs, 2),
+            "sample": f"{len(rows)} seeded query rows x {cfg.n_q_heads} heads of the 128K prefill workload "
+                      f"({pairs} visible pairs per head)",
+            "gpu_vs_oracle_max_abs_on_sample": float(err.max()), "gpu_vs_oracle_mean_abs_on_sample": float(err.mean())}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,179 @@
+/*
+ * ksa.h -- C ABI of the MI355X (gfx950) Kwai Summary Attention hot path.
+ *
+ * The library computes  O = softmax(Q K^T * scale + M_KSA) V  (the KSA attention formula of the
+ * paper's distillation section) over the augmented sequence of section 2.2.1 / Eq. 1, in which
+ * n_summary summary tokens follow every chunk of chunk_len text tokens, with the visibility M_KSA
+ * of section 2.2.2 / Eq. 3:
+ *   - a text token in chunk j sees the text of chunks max(0, j - window_chunks) .. j up to itself,
+ *     and the summary tokens of chunks 0 .. j - window_chunks - 1 (summaries of chunks still inside
+ *     the window are not visible);
+ *   - a summary token sees the text of its own chunk, itself, and the earlier summary tokens of
+ *     its own chunk (KSA_FLAG_SUMMARY_SELF_ONLY drops the earlier siblings).
+ * The paper has one summary token per chunk (n_summary = 1, chunk_len = k); n_summary > 1 with
+ * compress_ratio = chunk_len / n_summary is this library's generalisation of it.
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary.  Every function returns a ksa_status (0 = OK).
+ *   - "host" / "device" is stated for every pointer.  The caller owns every tensor and the stream;
+ *     the library owns the opaque ksa_layout until ksa_layout_destroy.
+ *   - Argument validation happens before any HIP call, so bad arguments are reported even on a
+ *     machine without a GPU.  Inputs are never written.
+ *   - Kernels are enqueued on the caller's HIP stream and are asynchronous; nothing synchronises.
+ *   - Tensor element type is bf16 (q, k, v, o, caches); log-sum-exp outputs are fp32.
+ *     Scores and accumulators are fp32; P is rounded to bf16 before the P V product in prefill.
+ */
+#ifndef KSA_H_
+#define KSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ksa_status {
+    KSA_OK = 0,
+    KSA_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, n_text % chunk_len != 0, ... */
+    KSA_ERR_UNSUPPORTED = -2,        /* head_dim / group size the kernels were not built for        */
+    KSA_ERR_WORKSPACE_TOO_SMALL = -3,
+    KSA_ERR_HIP = -4,                /* a HIP runtime call failed (no device, launch error, OOM)    */
+    KSA_ERR_OUT_OF_RANGE = -5        /* an index argument lies outside the layout                   */
+} ksa_status;
+
+#define KSA_FLAG_SUMMARY_SELF_ONLY 1u /* summary rows see, among summaries, only themselves */
+
+/* Problem statement, in the paper's terms (Eq. 1-3; Table "model_config"). */
+typedef struct ksa_params {
+    int32_t batch;           /* B                                                               */
+    int32_t n_text;          /* n: text tokens per sequence (prefill); context capacity (decode) */
+    int32_t chunk_len;       /* c: text tokens per chunk; n_text % chunk_len must be 0           */
+    int32_t n_summary;       /* m: summary tokens after each chunk (paper: 1); 0 = no summaries  */
+    int32_t compress_ratio;  /* k = c / m; validated (k * m == c) when m > 0, ignored when m == 0 */
+    int32_t window_chunks;   /* C >= 0: previous chunks whose text stays visible (Eq. 2 / Eq. 3)  */
+    int32_t n_q_heads;       /* Hq, a multiple of n_kv_heads (GQA: query head h reads KV head h / (Hq/Hkv)) */
+    int32_t n_kv_heads;      /* Hkv                                                              */
+    int32_t head_dim;        /* d: 64 or 128                                                     */
+    float softmax_scale;     /* <= 0 selects 1/sqrt(head_dim)                                    */
+    uint32_t flags;          /* KSA_FLAG_*                                                       */
+} ksa_params;
+
+typedef struct ksa_layout ksa_layout;
+
+/* Key-tile kinds reported by ksa_layout_tile_pairs. */
+#define KSA_TILE_FULL 0    /* every (query row, key) pair of the tile pair is visible: no mask applied */
+#define KSA_TILE_MASKED 1  /* per-element bounds are applied                                          */
+/* Index spaces of a tile: compact text index i (0..n-1) or compact summary ordinal u (0..J*m-1). */
+#define KSA_SPACE_TEXT 0
+#define KSA_SPACE_SUMMARY 1
+
+/*
+ * ksa_build_layout: the integer side of Eq. 1 and Eq. 3 -- index maps of the augmented sequence,
+ * per-row visible ranges, and the block-sparse schedule that lists, for every query tile, only the
+ * key tiles that hold at least one visible pair (section 2.3: only non-zero block pairs are loaded).
+ * Pure host work; touches no GPU.  *out (host) receives a new layout owned by the library.
+ * Errors: INVALID_ARG for bad params (see ksa_params), UNSUPPORTED for head_dim not in {64, 128}.
+ */
+int ksa_build_layout(const ksa_params *params /*host*/, ksa_layout **out /*host*/);
+void ksa_layout_destroy(ksa_layout *layout);
+
+/*
+ * Copies the schedule to the current HIP device (one hipMalloc + one hipMemcpy).  ksa_prefill_fwd
+ * does this itself on first use; calling it ahead keeps the first timed call allocation-free.
+ */
+int ksa_layout_upload(ksa_layout *layout);
+
+/* ---- introspection (host arrays, caller-allocated) used by the bit-exact layout tests ---------- */
+
+/* L = (n/c) * (c+m) augmented rows, J = n/c chunks, and the query / key tile heights of the schedule. */
+int ksa_layout_dims(const ksa_layout *layout, int64_t *aug_len, int32_t *n_chunks, int32_t *q_tile_rows,
+                    int32_t *k_tile_rows);
+/* Eq. 1 index maps.  aug_chunk, aug_is_summary, position_ids: [L]; text_to_aug: [n]; summary_to_aug: [J*m].
+ * position_ids gives a summary token the position of its chunk's last text token (section 2.2.1).
+ * Any pointer may be NULL to skip that array. */
+int ksa_layout_index_maps(const ksa_layout *layout, int32_t *aug_chunk, uint8_t *aug_is_summary,
+                          int32_t *position_ids, int32_t *text_to_aug, int32_t *summary_to_aug);
+/* Visible ranges of augmented row aq: out = {summary_lo, summary_hi, text_lo, text_hi}: summary ordinals
+ * [summary_lo, summary_hi) and text indices [text_lo, text_hi) are visible, nothing else. */
+int ksa_layout_row_ranges(const ksa_layout *layout, int64_t aq, int32_t out[4]);
+/* Row aq of M_KSA expanded from the row ranges: row_out[ak] = 1 iff visible, ak in [0, L). */
+int ksa_layout_mask_row(const ksa_layout *layout, int64_t aq, uint8_t *row_out);
+/*
+ * The (query tile, key tile) pairs the prefill kernel visits, for one (batch, head).  Pass NULL arrays to
+ * get *n_pairs only.  Pair x: query rows [q_begin[x], q_begin[x]+q_count[x]) of space q_space[x], key rows
+ * [k_begin[x], k_begin[x]+k_count[x]) of space k_space[x], kind[x] = KSA_TILE_FULL or KSA_TILE_MASKED.
+ */
+int ksa_layout_tile_pairs(const ksa_layout *layout, int64_t *n_pairs, uint8_t *q_space, int32_t *q_begin,
+                          int32_t *q_count, uint8_t *k_space, int32_t *k_begin, int32_t *k_count, uint8_t *kind);
+
+/*
+ * The prefill launch order: entry x is what workgroup x does -- the query tile (q_space[x], q_begin[x]) for
+ * batch[x] and q_head[x]; q_begin[x] = -1 marks a padding workgroup that does nothing.  Consecutive workgroup
+ * ids are dealt to the 8 XCDs round-robin, so entries congruent mod 8 share an L2.  NULL arrays: count only.
+ */
+int ksa_layout_launch_order(const ksa_layout *layout, int64_t *n_entries, uint8_t *q_space, int32_t *q_begin,
+                            int32_t *batch, int32_t *q_head);
+
+/* ---- prefill ------------------------------------------------------------------------------------ */
+
+/*
+ * ksa_prefill_fwd: attention output of all L augmented rows (text and summary rows alike).
+ *   q [B, L, Hq, d], k and v [B, L, Hkv, d], o [B, L, Hq, d]: device, bf16, last dim contiguous;
+ *   *_strides = {batch, row, head} strides in elements; NULL = contiguous in the order above.
+ *   lse: device fp32 [B, Hq, L] contiguous, natural-log sum-exp of the scaled visible scores; may be NULL.
+ *   stream: hipStream_t (NULL = default stream).
+ * The kernel walks the layout's schedule: bf16 MFMA for Q K^T and P V, fp32 online softmax.
+ * Errors: INVALID_ARG (null tensors, misaligned pointers: 16-byte alignment required), HIP.
+ */
+int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void *v, void *o, float *lse,
+                    const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
+                    void *stream);
+
+/* ---- decode over the summary KV cache (section 2.3.1) ------------------------------------------ */
+
+/*
+ * Cache geometry of this library (one K and one V tensor, device bf16, [B, Hkv, cache_rows, d]):
+ *   rows [0, S_cap)                         Summary Token Buffer: summary ordinal u = j*m + slot at row u;
+ *   rows [S_cap, S_cap + (C+1)*c)           text ring: text index i of chunk j = i / c at row
+ *                                           S_cap + (j mod (C+1)) * c + i mod c.
+ * S_cap = (n_text / c) * m.  The chunk being written overwrites, in place, the chunk that just left the
+ * window, so no copy is needed when a chunk completes.  Summaries of in-window chunks are resident in the
+ * buffer but are not read (Eq. 3).
+ */
+int ksa_cache_geometry(const ksa_params *params /*host*/, int32_t *summary_capacity, int32_t *cache_rows);
+/* Cache row of text index i / of summary ordinal u (host helpers for packing a cache). */
+int ksa_cache_text_row(const ksa_params *params, int64_t text_index, int32_t *row);
+int ksa_cache_summary_row(const ksa_params *params, int64_t summary_ordinal, int32_t *row);
+/*
+ * Rows a new text token at text index pos reads: up to three (offset, length) row ranges, in the order
+ * summaries, ring part 1, ring part 2; unused ranges have length 0.  out = {off0, len0, off1, len1, off2, len2}.
+ */
+int ksa_decode_ranges(const ksa_params *params /*host*/, int64_t pos, int32_t out[6]);
+
+/* Bytes of device workspace ksa_decode_fwd needs for the given number of key splits (0 = library default). */
+size_t ksa_decode_workspace_bytes(const ksa_params *params, int32_t n_splits);
+
+/*
+ * ksa_decode_fwd: one new text token per sequence.
+ *   q [B, Hq, d] device bf16 contiguous; k_cache, v_cache device bf16 with cache_strides = {batch, head, row}
+ *   in elements (NULL = contiguous [B, Hkv, cache_rows, d]); pos: device int32 [B], text index of the new
+ *   token, whose K/V must already be in the cache; o [B, Hq, d] device bf16; lse device fp32 [B, Hq] or NULL.
+ *   workspace: device, at least ksa_decode_workspace_bytes(params, n_splits); n_splits = 0 picks a default.
+ * Split-K over the visible rows: each workgroup streams one span of K and V rows once for all Hq/Hkv query
+ * heads of a KV head and writes a partial (max, sum, o); a second kernel merges the spans by log-sum-exp.
+ * Sequences whose pos is outside [0, n_text) produce NaN rows (device-side positions cannot be validated
+ * on the host without a synchronisation).
+ */
+int ksa_decode_fwd(const ksa_params *params /*host*/, const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
+                   size_t workspace_bytes, int32_t n_splits, void *stream);
+
+const char *ksa_status_string(int status);
+/* Static description of the build: tile sizes and the gfx target, e.g. for logs. */
+const char *ksa_build_info(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KSA_H_ */

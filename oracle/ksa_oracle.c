@@ -35,11 +35,15 @@
  *            text slot t of sequence b holds text index txt_base[b] + t
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
 #define KSA_ORACLE_FLAG_SUMMARY_SELF_ONLY 1u
+
+/* Threads the parallel loops below will use (for reporting next to timings). */
+int ksa_oracle_num_threads(void) { return omp_get_max_threads(); }
 
 /* ------------------------------------------------------------------------- */
 /* Eq. 1: the augmented sequence.  Position a lies in chunk a / (c+m); the   */

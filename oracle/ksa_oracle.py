@@ -55,6 +55,11 @@ def _ptr(a):
     return a.ctypes.data_as(C.c_void_p)
 
 
+def num_threads():
+    lib().ksa_oracle_num_threads.restype = C.c_int
+    return int(lib().ksa_oracle_num_threads())
+
+
 def aug_len(n, c, m):
     return int(lib().ksa_oracle_aug_len(n, c, m))
 

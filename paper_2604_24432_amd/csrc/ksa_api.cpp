@@ -1,0 +1,131 @@
+// C-ABI entry points that touch the GPU: schedule upload, prefill and decode launches.
+// Every argument check happens before the first HIP call.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "ksa_internal.h"
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void default_strides(int64_t out[3], const int64_t *given, int64_t d0, int64_t d1, int64_t d2) {
+    // contiguous [x, d0-dim, d1-dim, d2] -> strides of the three leading dims
+    if (given) {
+        out[0] = given[0], out[1] = given[1], out[2] = given[2];
+    } else {
+        out[2] = d2;
+        out[1] = d1 * d2;
+        out[0] = d0 * d1 * d2;
+    }
+}
+
+bool strides_ok(const int64_t s[3]) {
+    // rows must keep 16-byte alignment of the head vectors (bf16: multiples of 8 elements)
+    return s[0] >= 0 && s[1] > 0 && s[2] > 0 && s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+void ksa_layout_destroy(ksa_layout *lay) {
+    if (!lay) return;
+    if (lay->d_items) (void)hipFree(lay->d_items);
+    if (lay->d_entries) (void)hipFree(lay->d_entries);
+    delete lay;
+}
+
+int ksa_layout_upload(ksa_layout *lay) {
+    if (!lay) return KSA_ERR_INVALID_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return KSA_ERR_HIP;
+    if (lay->d_items && lay->device == dev) return KSA_OK;
+    if (lay->d_items) {
+        (void)hipFree(lay->d_items);
+        (void)hipFree(lay->d_entries);
+        lay->d_items = lay->d_entries = nullptr;
+    }
+    const size_t ib = lay->items.size() * sizeof(KsaWorkItem), eb = lay->entries.size() * sizeof(KsaWgEntry);
+    if (hipMalloc(&lay->d_items, ib) != hipSuccess) return KSA_ERR_HIP;
+    if (hipMalloc(&lay->d_entries, eb) != hipSuccess) {
+        (void)hipFree(lay->d_items);
+        lay->d_items = nullptr;
+        return KSA_ERR_HIP;
+    }
+    if (hipMemcpy(lay->d_items, lay->items.data(), ib, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(lay->d_entries, lay->entries.data(), eb, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(lay->d_items);
+        (void)hipFree(lay->d_entries);
+        lay->d_items = lay->d_entries = nullptr;
+        return KSA_ERR_HIP;
+    }
+    lay->device = dev;
+    return KSA_OK;
+}
+
+int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v, void *o, float *lse,
+                    const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
+                    void *stream) {
+    if (!lay || !q || !k || !v || !o) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return KSA_ERR_INVALID_ARG;
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return KSA_ERR_INVALID_ARG;
+    const ksa_params &p = lay->p;
+    KsaPrefillLaunch a;
+    default_strides(a.q_strides, q_strides, lay->aug_len, p.n_q_heads, p.head_dim);
+    default_strides(a.kv_strides, kv_strides, lay->aug_len, p.n_kv_heads, p.head_dim);
+    default_strides(a.o_strides, o_strides, lay->aug_len, p.n_q_heads, p.head_dim);
+    if (!strides_ok(a.q_strides) || !strides_ok(a.kv_strides) || !strides_ok(a.o_strides)) return KSA_ERR_INVALID_ARG;
+    const int rc = ksa_layout_upload(lay);
+    if (rc != KSA_OK) return rc;
+    a.q = q, a.k = k, a.v = v, a.o = o, a.lse = lse;
+    a.items = static_cast<const KsaWorkItem *>(lay->d_items);
+    a.entries = static_cast<const KsaWgEntry *>(lay->d_entries);
+    a.n_entries = (int32_t)lay->entries.size();
+    a.p = p;
+    a.aug_len = lay->aug_len;
+    return ksa_launch_prefill(a, stream);
+}
+
+size_t ksa_decode_workspace_bytes(const ksa_params *p, int32_t n_splits) {
+    if (ksa_validate_params(p) != KSA_OK || n_splits < 0) return 0;
+    if (n_splits == 0) n_splits = ksa_decode_default_splits(p);
+    // per (batch, query head, split): head_dim partial outputs + running max + running sum, fp32
+    return (size_t)p->batch * p->n_q_heads * n_splits * (p->head_dim + 2) * sizeof(float);
+}
+
+int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
+                   size_t workspace_bytes, int32_t n_splits, void *stream) {
+    int32_t s_cap = 0, rows = 0;
+    const int rc = ksa_cache_geometry(p, &s_cap, &rows);
+    if (rc != KSA_OK) return rc;
+    if (!q || !k_cache || !v_cache || !pos || !o || !workspace) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o) || !aligned16(workspace))
+        return KSA_ERR_INVALID_ARG;
+    if (n_splits < 0 || n_splits > 1024) return KSA_ERR_INVALID_ARG;
+    if (p->n_q_heads / p->n_kv_heads > 8) return KSA_ERR_UNSUPPORTED;
+    if (n_splits == 0) n_splits = ksa_decode_default_splits(p);
+    if (workspace_bytes < ksa_decode_workspace_bytes(p, n_splits)) return KSA_ERR_WORKSPACE_TOO_SMALL;
+    KsaDecodeLaunch a;
+    default_strides(a.cache_strides, cache_strides, p->n_kv_heads, rows, p->head_dim);
+    if (!strides_ok(a.cache_strides)) return KSA_ERR_INVALID_ARG;
+    a.q = q, a.k_cache = k_cache, a.v_cache = v_cache, a.pos = pos, a.o = o, a.lse = lse;
+    a.workspace = static_cast<float *>(workspace);
+    a.n_splits = n_splits;
+    a.summary_capacity = s_cap;
+    a.p = *p;
+    if (a.p.softmax_scale <= 0.f) a.p.softmax_scale = 1.0f / __builtin_sqrtf((float)p->head_dim);
+    return ksa_launch_decode(a, stream);
+}
+
+const char *ksa_build_info(void) {
+    static char info[160];
+    std::snprintf(info, sizeof(info), "libksa gfx950 q_tile=%d k_tile=%d max_segments=%d", KSA_Q_TILE, KSA_K_TILE,
+                  KSA_MAX_SEGMENTS);
+    return info;
+}
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+// Internal declarations shared by the host-side translation units of libksa.
+#ifndef KSA_INTERNAL_H_
+#define KSA_INTERNAL_H_
+
+#include <vector>
+
+#include "ksa.h"
+#include "ksa_schedule.h"
+
+struct ksa_layout {
+    ksa_params p;
+    int64_t aug_len;      // L
+    int32_t n_chunks;     // J
+    std::vector<KsaWorkItem> items;   // one per query tile, heaviest first
+    std::vector<KsaWgEntry> entries;  // one per workgroup of the prefill launch
+    // device copies (owned), valid on `device` once uploaded
+    int device = -1;
+    void *d_items = nullptr;
+    void *d_entries = nullptr;
+};
+
+// Validates the problem statement; returns KSA_OK or the error.
+int ksa_validate_params(const ksa_params *p);
+
+// Launchers implemented in the .hip files.  All pointers device, strides in elements.
+struct KsaPrefillLaunch {
+    const void *q, *k, *v;
+    void *o;
+    float *lse;
+    int64_t q_strides[3], kv_strides[3], o_strides[3];
+    const KsaWorkItem *items;
+    const KsaWgEntry *entries;
+    int32_t n_entries;
+    ksa_params p;
+    int64_t aug_len;
+};
+int ksa_launch_prefill(const KsaPrefillLaunch &a, void *stream);
+
+struct KsaDecodeLaunch {
+    const void *q, *k_cache, *v_cache;
+    const int32_t *pos;
+    void *o;
+    float *lse;
+    int64_t cache_strides[3];
+    float *workspace;
+    int32_t n_splits;
+    int32_t summary_capacity;
+    ksa_params p;
+};
+int ksa_launch_decode(const KsaDecodeLaunch &a, void *stream);
+int ksa_decode_default_splits(const ksa_params *p);
+
+#endif

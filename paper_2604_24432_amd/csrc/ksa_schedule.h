@@ -1,0 +1,43 @@
+// Schedule records shared by the host scheduler and the prefill kernel (plain structs, no logic).
+#ifndef KSA_SCHEDULE_H_
+#define KSA_SCHEDULE_H_
+
+#include <stdint.h>
+
+// Heights of the tiles the schedule is cut into.  A query tile is KSA_Q_TILE consecutive rows of one
+// index space (compact text indices or compact summary ordinals); a key tile is KSA_K_TILE rows.
+#define KSA_Q_TILE 128
+#define KSA_K_TILE 64
+#define KSA_MAX_SEGMENTS 5
+#define KSA_NUM_XCD 8
+
+// A run of consecutive key rows of one index space, walked in steps of KSA_K_TILE from `begin`.
+// masked == 0: every row of the query tile sees every key of the run (its length is a multiple of
+// KSA_K_TILE); masked == 1: the kernel clips each query row's visible range to [begin, end).
+struct KsaSegment {
+    int32_t space;   // KSA_SPACE_TEXT / KSA_SPACE_SUMMARY
+    int32_t begin;
+    int32_t end;
+    int32_t masked;
+};
+
+// One query tile and the key runs that hold all of its visible keys.
+struct KsaWorkItem {
+    int32_t q_space;
+    int32_t q_begin;
+    int32_t q_count;   // <= KSA_Q_TILE
+    int32_t n_seg;
+    KsaSegment seg[KSA_MAX_SEGMENTS];
+    int32_t n_tiles;   // key tiles over all segments (the item's cost)
+    int32_t pad[3];
+};
+
+// What workgroup blockIdx.x does: item < 0 means nothing.
+struct KsaWgEntry {
+    int32_t item;
+    int32_t batch;
+    int32_t q_head;
+    int32_t pad;
+};
+
+#endif
