@@ -257,7 +257,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             tmax = fmaxf(tmax, other_half(tmax));
             const float m_new = fmaxf(m_run[qb], tmax);
             const float msl = m_new * a.scale_log2e;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * a.scale_log2e - msl);
+            // (m_old - m_new) first: equal maxima (also the -1e30 start value) must give exactly 2^0
+            const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * a.scale_log2e);
             m_run[qb] = m_new;
             float rsum = 0.f;
 #pragma unroll
