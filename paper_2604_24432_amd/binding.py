@@ -14,7 +14,7 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libksa.so")
+LIB_PATH = os.environ.get("KSA_LIB", os.path.join(_HERE, "libksa.so"))
 
 KSA_FLAG_SUMMARY_SELF_ONLY = 1
 KSA_TILE_FULL, KSA_TILE_MASKED = 0, 1

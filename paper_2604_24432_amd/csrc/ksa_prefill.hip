@@ -1,17 +1,26 @@
 // KSA prefill forward for gfx950: flash-style online softmax over the live key tiles of the schedule.
 //
-// One workgroup (4 wavefronts of 64 lanes) owns one query tile of one (batch, query head).  Each wave
-// owns 32*QB query rows.  Scores are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16:
-// the 32x32 result block gives lane l the query column l%32 and the key rows 8*(g/4) + 4*(l/32) + g%4
-// for its 16 registers g, so
-//   - the softmax statistics of a query row live in one lane pair (l, l^32): the row max / sum are
+// One workgroup (4 wavefronts of 64 lanes, one per SIMD) owns one query tile of one (batch, query head);
+// each wave owns 32*QB query rows.  Scores are produced TRANSPOSED, S^T = K Q^T, with
+// v_mfma_f32_32x32x16_bf16: the 32x32 result block gives lane l the query column l%32 and the key rows
+// 8*(g/4) + 4*(l/32) + g%4 for its 16 registers g, so
+//   - the softmax statistics of a query row live in one lane pair (l, l^32): row max and row sum are
 //     in-lane reductions plus one v_permlane32_swap, no LDS, no shuffle tree;
 //   - the same registers, rounded to bf16, are already the B operand of O^T += V^T P^T (eight registers
 //     of one lane = eight k slots), so P never leaves the register file;
 //   - the rescale factor of the output accumulator is a per-lane scalar.
-// K and V tiles (64 keys) are staged in LDS with an XOR swizzle of the 16-byte chunks; the K operand is
-// read with ds_read_b128, the V^T operand with the gfx950 transposing read ds_read_b64_tr_b16, which hands
-// each lane four consecutive keys of one head-dim column out of a row-major [key][d] tile.
+// K and V tiles (64 keys) go from global memory straight into LDS (global_load_lds_dwordx4, no VGPR
+// staging) with an XOR swizzle of the 16-byte chunks applied on the global side; the K operand is read
+// with ds_read_b128, the V^T operand with the gfx950 transposing read ds_read_b64_tr_b16, which hands each
+// lane four consecutive keys of one head-dim column out of the row-major [key][d] tile.
+//
+// Two loops share the accumulators.  Runs of FULL tiles (no mask; almost all of the work at long context:
+// text rows against distant summaries) take a software-pipelined loop with double-buffered LDS in which the
+// score MFMAs of tile t+1 are issued next to the softmax arithmetic of tile t.  MASKED runs (window edges,
+// the causal diagonal, summary rows) take a plain loop that clips every query row to its visible range.
+// The running maximum is only raised when a tile exceeds it by more than 2^8 in the exponent domain, so the
+// accumulator rescale almost never runs; results are unchanged because the final 1/l normalisation uses
+// the same reference.
 //
 // Rows are addressed in two compact index spaces, text index i and summary ordinal u (Eq. 1):
 //   augmented row of text i    = (i / c) * (c + m) + i % c
@@ -30,11 +39,21 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+#define LDS_PTR(T) __attribute__((address_space(3))) T *
+#define GLOBAL_PTR(T) __attribute__((address_space(1))) T *
+
+#ifndef KSA_SB
+#define KSA_SB 1
+#endif
+#ifndef KSA_SGB
+#define KSA_SGB 0
+#endif
 constexpr int NW = 4;                         // waves per workgroup
 constexpr int BN = KSA_K_TILE;                // keys per tile
 constexpr int QB = KSA_Q_TILE / (NW * 32);    // 32-row query blocks per wave
 static_assert(KSA_Q_TILE == NW * QB * 32, "query tile must be a whole number of 32-row blocks per wave");
 static_assert(BN == 64, "key tile is two 32-key MFMA blocks");
+constexpr float RESCALE_THRESHOLD_LOG2 = 8.0f;   // raise the running max only for a jump above 2^8
 
 struct PrefillArgs {
     const __bf16 *q, *k, *v;
@@ -67,45 +86,219 @@ __device__ __forceinline__ float other_half(float x) {
     // value held by lane l^32
     const unsigned u = __builtin_bit_cast(unsigned, x);
     auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    const unsigned mine_is_low = threadIdx.x & 32 ? r[0] : r[1];
-    return __builtin_bit_cast(float, mine_is_low);
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+// LDS tile: row-major [64][D] bf16, the 16-byte chunk index XORed with a function of the row
+template <int D>
+__device__ __forceinline__ int k_swz(int row) { return row & (D / 8 - 1); }
+template <int D>
+__device__ __forceinline__ int v_swz(int row) { return ((row & 3) << 2) & (D / 8 - 1); }
+
+template <int D>
+struct Tile {
+    static constexpr int CH = D / 8;           // 16-byte chunks per row
+    static constexpr int RPI = 64 / CH;        // rows covered by one wavefront load instruction
+    static constexpr int NI = 16 / RPI;        // load instructions per wave per tile (16 rows per wave)
+    static constexpr int KS = D / 16;          // k steps of the score MFMA
+    static constexpr int DB = D / 32;          // 32-column blocks of the output
+    static constexpr int BYTES = BN * D * 2;
+};
+
+// Per-lane element offsets (relative to the tile's first row) of the 16-byte pieces this lane fetches.
+template <int D>
+struct LaneOffsets {
+    int k[Tile<D>::NI], v[Tile<D>::NI];
+};
+
+// Offsets for the tile whose first key is kt; rows beyond `last` (inclusive bound) are clamped to it.
+template <int D>
+__device__ __forceinline__ void lane_offsets(const PrefillArgs &a, int space, int kt, int last, int wave, int lane,
+                                             int base_aug, LaneOffsets<D> &off) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int i = 0; i < T::NI; ++i) {
+        const int row = 16 * wave + T::RPI * i + lane / T::CH;
+        const int pch = lane % T::CH;
+        int kc = kt + row;
+        kc = kc < last ? kc : last;
+        const int rel = (aug_row(a, space, kc) - base_aug) * (int)a.ks[1];
+        off.k[i] = rel + ((pch ^ k_swz<D>(row)) << 3);
+        off.v[i] = rel + ((pch ^ v_swz<D>(row)) << 3);
+    }
 }
 
 template <int D>
-__device__ __forceinline__ int k_tile_off(int row, int chunk) {
-    return row * (D * 2) + ((chunk ^ (row & (D / 8 - 1))) << 4);
+__device__ __forceinline__ void issue_tile_load(const __bf16 *gbase, const int (&off)[Tile<D>::NI], unsigned char *lds,
+                                                int buf_off, int wave) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int i = 0; i < T::NI; ++i) {
+        unsigned char *dst = lds + buf_off + (16 * wave + T::RPI * i) * (D * 2);   // wave-uniform; lanes land 16 B apart
+        __builtin_amdgcn_global_load_lds((const GLOBAL_PTR(void))(gbase + off[i]), (LDS_PTR(void))dst, 16, 0, 0);
+    }
 }
+
+// Byte addresses inside an LDS tile are written as (per-lane constant XOR small constant) + constant, so that
+// a handful of registers plus the instructions' immediate offsets cover every operand read.
+struct LaneLds {
+    int k;   // K operand: row r, chunk (swizzle(r) ^ h); XOR (s << 5) selects k step s
+    int v;   // V^T operand: this lane's address row / column of the transposing read; XOR (db << 6) selects the column block
+};
+
 template <int D>
-__device__ __forceinline__ int v_tile_off(int row, int chunk) {
-    return row * (D * 2) + ((chunk ^ (((row & 3) << 2) & (D / 8 - 1))) << 4);
+__device__ __forceinline__ LaneLds lane_lds(int lane) {
+    const int r = lane & 31, h = lane >> 5;
+    const int grp = lane >> 4, li = lane & 15;
+    // transposing read: lane (grp, li) supplies the address of key 4*(grp/2) + li/4, columns 16*(grp%2) + 4*(li%4) .. +3
+    // and receives keys 4*(grp/2) .. +3 of column 16*(grp%2) + li
+    const int t_row = 4 * (grp >> 1) + (li >> 2);
+    const int t_col = 16 * (grp & 1) + 4 * (li & 3);
+    LaneLds L;
+    L.k = r * (D * 2) + ((k_swz<D>(r) ^ h) << 4);
+    L.v = t_row * (D * 2) + (((t_col >> 3) ^ v_swz<D>(t_row)) << 4) + ((t_col & 7) << 1);
+    return L;
+}
+
+// S^T (two 32-key blocks) for QB query blocks: sacc[qb][kb] += K[kb] Q[qb]^T
+template <int D>
+__device__ __forceinline__ void score_mfma(const unsigned char *lds, int buf_off, const LaneLds &ll,
+                                           const bf16x8 (&qreg)[QB][Tile<D>::KS], f32x16 (&sacc)[QB][2]) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) sacc[qb][kb][g] = 0.f;
+#pragma unroll
+    for (int s = 0; s < T::KS; ++s) {
+        const int a_s = ll.k ^ (s << 5);   // logical chunk 2s + h of row r
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(lds + a_s + (buf_off + kb * 32 * (D * 2)));
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
+        }
+    }
+}
+
+// O^T += V^T P^T
+template <int D>
+__device__ __forceinline__ void pv_mfma(const unsigned char *lds, int buf_off, const LaneLds &ll,
+                                        const bf16x8 (&pb)[QB][2][2], f32x16 (&oacc)[QB][Tile<D>::DB]) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int db = 0; db < T::DB; ++db) {
+        const int a_db = ll.v ^ (db << 6);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int o0 = buf_off + (kb * 32 + hf * 16) * (D * 2), o1 = o0 + 8 * (D * 2);
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a_db + o0));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a_db + o1));
+                const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kb][hf], oacc[qb][db], 0, 0, 0);
+            }
+    }
+}
+
+// Online-softmax state of one lane's query rows.  m_ref is the reference maximum (raw score units) the
+// exponentials are taken against; l_part is this lane's part of the row sum (the lane pair is added up at
+// the end).
+struct RowState {
+    float m_ref[QB], l_part[QB];
+};
+
+// Row maxima of a score tile; returns true if some lane's row exceeds its reference by more than the threshold.
+__device__ __forceinline__ bool tile_max(const f32x16 (&sacc)[QB][2], const RowState &st, float sl, float (&tmax)[QB]) {
+    bool raise = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        float mx = sacc[qb][0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) mx = fmaxf(mx, sacc[qb][kb][g]);
+        mx = fmaxf(mx, other_half(mx));
+        tmax[qb] = mx;
+        raise |= (mx - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+    }
+    return __builtin_amdgcn_ballot_w64(raise) != 0;   // wave-uniform
+}
+
+// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators.
+template <int D>
+__device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
+                                                float sl) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(st.m_ref[qb], tmax[qb]);
+        // (old - new) first: equal references (also the -1e30 start value) must give exactly 2^0
+        const float alpha = __builtin_amdgcn_exp2f((st.m_ref[qb] - m_new) * sl);
+        st.m_ref[qb] = m_new;
+        st.l_part[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < T::DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
+    }
+}
+
+// p = 2^((s - m_ref) * scale * log2 e) rounded to bf16 in the B-operand layout of P V.  The row sum adds up the
+// ROUNDED values (v_dot2c_f32_bf16 against (1, 1)), so that O = sum(p v) / sum(p) is normalised by exactly the
+// weights that were multiplied: a row dominated by one key returns that key's V row up to output rounding.
+__device__ __forceinline__ void exp_and_pack(const f32x16 (&sacc)[QB][2], bf16x8 (&pb)[QB][2][2], RowState &st, float sl) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float msl = st.m_ref[qb] * sl;
+        float rsum = st.l_part[qb];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 16; g += 2) {
+                bf16x2 pk;
+                pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][g], sl, -msl));
+                pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][g + 1], sl, -msl));
+                rsum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum, false);
+                pb[qb][kb][g / 8][g % 8] = pk[0];
+                pb[qb][kb][g / 8][g % 8 + 1] = pk[1];
+            }
+        st.l_part[qb] = rsum;
+    }
 }
 
 template <int D>
 __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs a) {
-    constexpr int CH = D / 8;            // 16-byte chunks per row
-    constexpr int RPP = NW * 64 / CH;    // tile rows loaded per pass of the workgroup
-    constexpr int NP = BN / RPP;         // passes per tile
-    constexpr int KS = D / 16;           // k steps of the score MFMA
-    constexpr int DB = D / 32;           // 32-column blocks of the output
-
-    __shared__ __attribute__((aligned(16))) unsigned char lds_k[BN * D * 2];
-    __shared__ __attribute__((aligned(16))) unsigned char lds_v[BN * D * 2];
+    using T = Tile<D>;
+    // two K tiles and two V tiles, back to back: buffer selection is an immediate offset
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * T::BYTES];
+    constexpr int K0 = 0, V0 = 2 * T::BYTES;   // second buffers follow at + T::BYTES
 
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
     const int b = ent.batch, hq = ent.q_head, hkv = hq / a.group;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
+    const LaneLds ll = lane_lds<D>(lane);
 
     const int q_space = item.q_space, q_begin = item.q_begin, q_end = item.q_begin + item.q_count;
     const int n_seg = item.n_seg;
 
     // ---- per-lane query rows: visible ranges (Eq. 3) and the Q operand -------------------------
-    int lo[QB][2], hi[QB][2];   // [.][space]
+    int lo_t[QB], hi_t[QB], lo_s[QB], hi_s[QB];   // text / summary ranges
     int q_aug[QB];
     bool q_valid[QB];
-    bf16x8 qreg[QB][KS];
+    bf16x8 qreg[QB][T::KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const int idx = q_begin + (wave * QB + qb) * 32 + r;
@@ -115,207 +308,178 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         if (q_space == KSA_SPACE_TEXT) {
             const int j = div_by(idc, a.c, a.c_shift);
             const int first = j - a.C > 0 ? j - a.C : 0;
-            lo[qb][KSA_SPACE_SUMMARY] = 0;
-            hi[qb][KSA_SPACE_SUMMARY] = first * a.m;
-            lo[qb][KSA_SPACE_TEXT] = first * a.c;
-            hi[qb][KSA_SPACE_TEXT] = idc + 1;
+            lo_s[qb] = 0;
+            hi_s[qb] = first * a.m;
+            lo_t[qb] = first * a.c;
+            hi_t[qb] = idc + 1;
         } else {
             const int j = div_by(idc, a.m, a.m_shift);
-            lo[qb][KSA_SPACE_SUMMARY] = a.self_only ? idc : j * a.m;
-            hi[qb][KSA_SPACE_SUMMARY] = idc + 1;
-            lo[qb][KSA_SPACE_TEXT] = j * a.c;
-            hi[qb][KSA_SPACE_TEXT] = (j + 1) * a.c;
+            lo_s[qb] = a.self_only ? idc : j * a.m;
+            hi_s[qb] = idc + 1;
+            lo_t[qb] = j * a.c;
+            hi_t[qb] = (j + 1) * a.c;
         }
         if (!q_valid[qb]) {
-            lo[qb][0] = lo[qb][1] = 0x7fffffff;
-            hi[qb][0] = hi[qb][1] = 0;
+            lo_s[qb] = lo_t[qb] = 0x7fffffff;
+            hi_s[qb] = hi_t[qb] = 0;
         }
         const __bf16 *qp = a.q + b * a.qs[0] + (int64_t)q_aug[qb] * a.qs[1] + hq * a.qs[2] + h * 8;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
+        for (int s = 0; s < T::KS; ++s) {
             if (q_valid[qb])
                 qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16);
             else
                 qreg[qb][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
         }
     }
-    // union of the wave's rows' ranges per space: a tile outside it is skipped by the whole wave
-    int wlo[2], whi[2];
+    // union of the wave's rows' ranges per space: a masked tile outside it is skipped by the whole wave
+    int wlo_t = lo_t[0], whi_t = hi_t[0], wlo_s = lo_s[0], whi_s = hi_s[0];
 #pragma unroll
-    for (int sp = 0; sp < 2; ++sp) {
-        int mn = lo[0][sp], mx = hi[0][sp];
-#pragma unroll
-        for (int qb = 1; qb < QB; ++qb) {
-            mn = min(mn, lo[qb][sp]);
-            mx = max(mx, hi[qb][sp]);
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            mn = min(mn, __shfl_xor(mn, off));
-            mx = max(mx, __shfl_xor(mx, off));
-        }
-        wlo[sp] = mn;
-        whi[sp] = mx;
+    for (int qb = 1; qb < QB; ++qb) {
+        wlo_t = min(wlo_t, lo_t[qb]), whi_t = max(whi_t, hi_t[qb]);
+        wlo_s = min(wlo_s, lo_s[qb]), whi_s = max(whi_s, hi_s[qb]);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        wlo_t = min(wlo_t, __shfl_xor(wlo_t, off)), whi_t = max(whi_t, __shfl_xor(whi_t, off));
+        wlo_s = min(wlo_s, __shfl_xor(wlo_s, off)), whi_s = max(whi_s, __shfl_xor(whi_s, off));
+    }
+    wlo_t = __builtin_amdgcn_readfirstlane(wlo_t), whi_t = __builtin_amdgcn_readfirstlane(whi_t);
+    wlo_s = __builtin_amdgcn_readfirstlane(wlo_s), whi_s = __builtin_amdgcn_readfirstlane(whi_s);
 
     // ---- accumulators -------------------------------------------------------------------------
-    f32x16 oacc[QB][DB];
-    float m_run[QB], l_run[QB];
+    f32x16 oacc[QB][T::DB];
+    RowState st;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -1e30f;
-        l_run[qb] = 0.f;
+        st.m_ref[qb] = -1e30f;
+        st.l_part[qb] = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < T::DB; ++db)
 #pragma unroll
             for (int g = 0; g < 16; ++g) oacc[qb][db][g] = 0.f;
     }
 
     const __bf16 *kbase = a.k + b * a.ks[0] + hkv * a.ks[2];
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
-    const int ld_chunk = tid % CH, ld_row = tid / CH;
+    const float sl = a.scale_log2e;
 
-    uint4 kreg[NP], vreg[NP];
-    auto fetch = [&](int seg, int kt) {
-        const int space = item.seg[seg].space, last = item.seg[seg].end - 1;
-#pragma unroll
-        for (int ps = 0; ps < NP; ++ps) {
-            int kc = kt + ps * RPP + ld_row;
-            kc = kc < last ? kc : last;   // rows past the run are clamped (and masked out below)
-            const int64_t off = (int64_t)aug_row(a, space, kc) * a.ks[1] + ld_chunk * 8;
-            kreg[ps] = *reinterpret_cast<const uint4 *>(kbase + off);
-            vreg[ps] = *reinterpret_cast<const uint4 *>(vbase + off);
-        }
-    };
+    for (int seg = 0; seg < n_seg; ++seg) {
+        const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
+        const bool masked = item.seg[seg].masked != 0;
+        const int n_tiles = (seg_end - seg_begin + BN - 1) / BN;
+        // Are the lanes' row offsets the same for every tile of the run?  Yes when every tile starts at the same
+        // phase of the chunk pattern (64 % period == 0), or never crosses a chunk (period % 64 == 0, aligned).
+        const int period = space == KSA_SPACE_TEXT ? a.c : a.m;
+        const bool invariant = (BN % period == 0) || (period % BN == 0 && seg_begin % BN == 0);
+        LaneOffsets<D> off;
+        if (invariant) lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
 
-    int seg = 0, kt = item.seg[0].begin;
-    fetch(seg, kt);
-
-    while (seg < n_seg) {
-        const int cur_seg = seg, cur_kt = kt;
-        kt += BN;
-        if (kt >= item.seg[seg].end) {
-            ++seg;
-            if (seg < n_seg) kt = item.seg[seg].begin;
-        }
-        __syncthreads();   // everyone is done reading the previous tile
+        if (!masked && invariant && n_tiles >= 3) {
+            // ================= pipelined loop over a run of FULL tiles ==================================
+            // P V lags one tile behind the scores: in iteration t the exponentials of tile t (VALU) are issued next
+            // to the MFMAs of O += P(t-1) V(t-1), and the score MFMAs of tile t run while the VALU is idle.
+            // LDS: K(t) in k buffer t&1, V(t) in v buffer t&1; loads of K(t+1), V(t) are issued in iteration t.
+            auto tile_base = [&](int t) { return (int64_t)aug_row(a, space, seg_begin + t * BN) * a.ks[1]; };
+            __syncthreads();   // earlier readers of the LDS buffers are done
+            issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
+            bf16x8 p_prev[QB][2][2];
+            for (int t = 0; t < n_tiles; ++t) {
+                const int cur = (t & 1) * T::BYTES, oth = T::BYTES - cur;
+                __builtin_amdgcn_s_waitcnt(0);   // this wave's pieces of K(t), V(t-1) have landed
+                __syncthreads();                 // ... and everyone's; all waves are past iteration t-1
+                if (t + 1 < n_tiles) issue_tile_load<D>(kbase + tile_base(t + 1), off.k, lds, K0 + oth, wave);
+                issue_tile_load<D>(vbase + tile_base(t), off.v, lds, V0 + cur, wave);
+#if KSA_SB
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+                f32x16 sacc[QB][2];
+                score_mfma<D>(lds, K0 + cur, ll, qreg, sacc);
+#if KSA_SB
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+                float tmax[QB];
+                if (tile_max(sacc, st, sl, tmax)) {
+                    // rare: the accumulators must take P(t-1) V(t-1) before they are rescaled
+                    if (t > 0) pv_mfma<D>(lds, V0 + oth, ll, p_prev, oacc);
+                    raise_reference<D>(st, tmax, oacc, sl);
+                    exp_and_pack(sacc, p_prev, st, sl);
+                } else {
+                    bf16x8 p_new[QB][2][2];
+                    exp_and_pack(sacc, p_new, st, sl);
+                    pv_mfma<D>(lds, V0 + oth, ll, p_prev, oacc);
+                    // one score MFMA's worth of VALU work per P V MFMA
 #pragma unroll
-        for (int ps = 0; ps < NP; ++ps) {
-            const int row = ps * RPP + ld_row;
-            *reinterpret_cast<uint4 *>(lds_k + k_tile_off<D>(row, ld_chunk)) = kreg[ps];
-            *reinterpret_cast<uint4 *>(lds_v + v_tile_off<D>(row, ld_chunk)) = vreg[ps];
-        }
-        __syncthreads();
-        if (seg < n_seg) fetch(seg, kt);   // next tile's global loads fly during this tile's math
-
-        const int space = item.seg[cur_seg].space;
-        const bool masked = item.seg[cur_seg].masked != 0;
-        const int seg_begin = item.seg[cur_seg].begin, seg_end = item.seg[cur_seg].end;
-        if (masked) {
-            const int t_lo = max(cur_kt, seg_begin), t_hi = min(cur_kt + BN, seg_end);
-            if (t_lo >= whi[space] || t_hi <= wlo[space]) continue;   // wave-uniform: nothing visible here
-        }
-
-        // ---- S^T = K Q^T ----------------------------------------------------------------------
-        f32x16 sacc[QB][2];
+                    for (int x = 0; x < KSA_SGB * QB * 2 * 2 * T::DB; ++x) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // exp
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads
+                    }
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int g = 0; g < 16; ++g) sacc[qb][kb][g] = 0.f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(lds_k + k_tile_off<D>(kb * 32 + r, 2 * s + h));
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
+                            for (int hf = 0; hf < 2; ++hf) p_prev[qb][kb][hf] = p_new[qb][kb][hf];
+                }
             }
+            // drain: P V of the last tile (V(n_tiles-1) sits in buffer (n_tiles-1)&1)
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            pv_mfma<D>(lds, V0 + ((n_tiles - 1) & 1) * T::BYTES, ll, p_prev, oacc);
+            continue;
         }
 
-        // ---- mask + online softmax ------------------------------------------------------------
-        bf16x8 pb[QB][2][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
+        // ================= plain loop: MASKED runs, short runs, odd chunk shapes ============================
+        const int wlo = space == KSA_SPACE_TEXT ? wlo_t : wlo_s, whi = space == KSA_SPACE_TEXT ? whi_t : whi_s;
+        for (int kt = seg_begin; kt < seg_end; kt += BN) {
+            const int t_lo = kt, t_hi = min(kt + BN, seg_end);
+            // the wave has nothing visible in this tile (block-diagonal summary rows, window edges): skip the math
+            const bool active = !masked || (t_lo < whi && t_hi > wlo);
+            const bool ragged = kt + BN > seg_end;
+            const int base_aug = aug_row(a, space, kt);
+            if (!invariant || ragged) lane_offsets<D>(a, space, kt, seg_end - 1, wave, lane, base_aug, off);
+            __syncthreads();
+            issue_tile_load<D>(kbase + (int64_t)base_aug * a.ks[1], off.k, lds, K0, wave);
+            issue_tile_load<D>(vbase + (int64_t)base_aug * a.ks[1], off.v, lds, V0, wave);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            if (!active) continue;
+            f32x16 sacc[QB][2];
+            score_mfma<D>(lds, K0, ll, qreg, sacc);
             if (masked) {
-                const int elo = max(lo[qb][space], seg_begin), ehi = min(hi[qb][space], seg_end);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int qb = 0; qb < QB; ++qb) {
+                    const int lo = space == KSA_SPACE_TEXT ? lo_t[qb] : lo_s[qb];
+                    const int hi = space == KSA_SPACE_TEXT ? hi_t[qb] : hi_s[qb];
+                    const int elo = max(lo, seg_begin), ehi = min(hi, seg_end);
 #pragma unroll
-                    for (int g = 0; g < 16; ++g) {
-                        const int key = cur_kt + kb * 32 + 8 * (g / 4) + 4 * h + (g % 4);
-                        if (key < elo || key >= ehi) sacc[qb][kb][g] = -INFINITY;
-                    }
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int g = 0; g < 16; ++g) {
+                            const int key = kt + kb * 32 + 8 * (g / 4) + 4 * h + (g % 4);
+                            if (key < elo || key >= ehi) sacc[qb][kb][g] = -INFINITY;
+                        }
+                }
             }
-            float tmax = sacc[qb][0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int g = 0; g < 16; ++g) tmax = fmaxf(tmax, sacc[qb][kb][g]);
-            tmax = fmaxf(tmax, other_half(tmax));
-            const float m_new = fmaxf(m_run[qb], tmax);
-            const float msl = m_new * a.scale_log2e;
-            // (m_old - m_new) first: equal maxima (also the -1e30 start value) must give exactly 2^0
-            const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * a.scale_log2e);
-            m_run[qb] = m_new;
-            float rsum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int g = 0; g < 16; ++g) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][g], a.scale_log2e, -msl));
-                    rsum += pv;
-                    pb[qb][kb][g / 8][g % 8] = (__bf16)pv;
-                }
-            rsum += other_half(rsum);
-            l_run[qb] = l_run[qb] * alpha + rsum;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T -------------------------------------------------------------------
-        {
-            const int grp = lane >> 4, li = lane & 15;
-            // lane (grp, li) supplies the address of key 4*(grp/2) + li/4, columns 16*(grp%2) + 4*(li%4) .. +3
-            const int t_row = 4 * (grp >> 1) + (li >> 2);
-            const int t_col = 16 * (grp & 1) + 4 * (li & 3);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    const int base = kb * 32 + hf * 16;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        const int col = db * 32 + t_col;
-                        const int o0 = v_tile_off<D>(base + t_row, col >> 3) + ((col & 7) << 1);
-                        const int o1 = v_tile_off<D>(base + 8 + t_row, col >> 3) + ((col & 7) << 1);
-                        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4 *)(lds_v + o0));
-                        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (__attribute__((address_space(3))) s16x4 *)(lds_v + o1));
-                        const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        const bf16x8 va = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb)
-                            oacc[qb][db] =
-                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kb][hf], oacc[qb][db], 0, 0, 0);
-                    }
-                }
+            bf16x8 pb[QB][2][2];
+            float tmax[QB];
+            if (tile_max(sacc, st, sl, tmax)) raise_reference<D>(st, tmax, oacc, sl);
+            exp_and_pack(sacc, pb, st, sl);
+            pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
     }
 
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+        const float l_row = st.l_part[qb] + other_half(st.l_part[qb]);
         if (!q_valid[qb]) continue;
-        const float inv = 1.0f / l_run[qb];
+        const float inv = 1.0f / l_row;
         __bf16 *op = a.o + b * a.os[0] + (int64_t)q_aug[qb] * a.os[1] + hq * a.os[2];
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < T::DB; ++db)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 bf16x4 pk;
@@ -324,7 +488,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 *reinterpret_cast<bf16x4 *>(op + db * 32 + g4 * 8 + h * 4) = pk;
             }
         if (a.lse && h == 0)
-            a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = m_run[qb] * a.scale + __logf(l_run[qb]);
+            a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
     }
 }
 
@@ -360,6 +524,12 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     a.scale = L.p.softmax_scale;
     a.scale_log2e = L.p.softmax_scale * 1.4426950408889634f;
     if (L.n_entries <= 0) return KSA_OK;
+    // lane offsets inside one tile are 32-bit element offsets: a tile of 64 rows of one index space spans at
+    // most (64 / period + 2) chunks of the augmented sequence
+    {
+        const int64_t period = a.m > 0 && a.m < a.c ? a.m : a.c;
+        if (L.kv_strides[1] * ((BN / period + 2) * (int64_t)a.w) >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (L.p.head_dim == 128)
         hipLaunchKernelGGL(ksa_prefill_kernel<128>, dim3(L.n_entries), dim3(NW * 64), 0, st, a);

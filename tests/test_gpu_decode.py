@@ -16,7 +16,8 @@ from oracle import ksa_oracle as O
 
 pytestmark = pytest.mark.gpu
 
-MAX_ABS, MEAN_ABS, LSE_ABS = 2e-2, 2e-3, 2e-3
+# LSE: the row sum adds bf16-rounded weights (relative error <= 2^-9), so |dLSE| <= 2^-9 = 1.95e-3 plus fp32 noise
+MAX_ABS, MEAN_ABS, LSE_ABS = 2e-2, 2e-3, 4e-3
 
 
 def say(msg):
