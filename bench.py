@@ -161,7 +161,7 @@ def cpu_baseline(cfg, q, k, v, o_gpu, flops_per_pair_all_heads):
     import torch
     from oracle import ksa_oracle as O
     gen = np.random.default_rng(12345)
-    rows = np.sort(gen.choice(cfg.aug_len, size=192, replace=False)).astype(np.int64)
+    rows = np.sort(gen.choice(cfg.aug_len, size=2400, replace=False)).astype(np.int64)
     qf, kf, vf = (x.float().cpu().numpy() for x in (q, k, v))
     t0 = time.perf_counter()
     o_ref, _ = O.prefill(qf, kf, vf, cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks, rows=rows)

@@ -16,8 +16,8 @@ from oracle import ksa_oracle as O
 
 pytestmark = pytest.mark.gpu
 
-# LSE: the row sum adds bf16-rounded weights (relative error <= 2^-9), so |dLSE| <= 2^-9 = 1.95e-3 plus fp32 noise
-MAX_ABS, MEAN_ABS, LSE_ABS = 2e-2, 2e-3, 4e-3
+# decode keeps its weights and sums in fp32, so the log-sum-exp is held to fp32 accuracy
+MAX_ABS, MEAN_ABS, LSE_ABS = 2e-2, 2e-3, 1e-4
 
 
 def say(msg):
