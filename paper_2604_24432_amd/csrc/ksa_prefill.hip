@@ -45,8 +45,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #ifndef KSA_SB
 #define KSA_SB 1
 #endif
-#ifndef KSA_SGB
-#define KSA_SGB 0
+#ifndef KSA_PIN
+#define KSA_PIN 1
 #endif
 constexpr int NW = 4;                         // waves per workgroup
 constexpr int BN = KSA_K_TILE;                // keys per tile
@@ -128,14 +128,24 @@ __device__ __forceinline__ void lane_offsets(const PrefillArgs &a, int space, in
     }
 }
 
+// global -> LDS without VGPR staging: every lane fetches 16 bytes from its own global address and the wave's 64
+// pieces land back to back (lane order) from the wave-uniform LDS address `dst`.
+// Written as inline assembly on purpose: for the builtin the compiler assumes that any later LDS read may alias the
+// data in flight and puts s_waitcnt vmcnt(0) in front of it, which serialises the loads with the MFMA work they are
+// meant to overlap.  Here the waits are explicit (s_waitcnt before the workgroup barrier that publishes a tile).
+// M0 carries the LDS address; no other code of this kernel uses M0.
+__device__ __forceinline__ void lds_direct_load_16(const __bf16 *src, const unsigned char *dst) {
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory");
+}
+
 template <int D>
 __device__ __forceinline__ void issue_tile_load(const __bf16 *gbase, const int (&off)[Tile<D>::NI], unsigned char *lds,
                                                 int buf_off, int wave) {
     using T = Tile<D>;
 #pragma unroll
     for (int i = 0; i < T::NI; ++i) {
-        unsigned char *dst = lds + buf_off + (16 * wave + T::RPI * i) * (D * 2);   // wave-uniform; lanes land 16 B apart
-        __builtin_amdgcn_global_load_lds((const GLOBAL_PTR(void))(gbase + off[i]), (LDS_PTR(void))dst, 16, 0, 0);
+        lds_direct_load_16(gbase + off[i], lds + buf_off + (16 * wave + T::RPI * i) * (D * 2));
     }
 }
 
@@ -232,10 +242,14 @@ __device__ __forceinline__ bool tile_max(const f32x16 (&sacc)[QB][2], const RowS
 }
 
 // Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators.
+// The accumulators live in accumulation registers (where the MFMAs want them).  The scaling is written as inline
+// assembly with AGPR operands: left to the compiler, the copies to ordinary VGPRs that a plain multiply needs are
+// hoisted out of this rarely taken block into the loop around it, where they drain the MFMA pipe on every tile.
 template <int D>
 __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
                                                 float sl) {
     using T = Tile<D>;
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // let the last MFMA results reach the register file
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float m_new = fmaxf(st.m_ref[qb], tmax[qb]);
@@ -246,8 +260,19 @@ __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
+            for (int g = 0; g < 16; ++g) {
+                float acc = oacc[qb][db][g], tmp;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(acc), "=&v"(tmp)
+                             : "v"(alpha));
+                oacc[qb][db][g] = acc;
+            }
     }
+    asm volatile("s_nop 7" ::: "memory");
+    // Register spills around this block are reloaded from scratch memory.  Waiting for them here keeps the compiler
+    // from placing its own s_waitcnt vmcnt(0) after the block rejoins the loop, where it would also wait for the
+    // LDS-direct tile loads in flight (the hardware counter is shared) on every tile.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
 }
 
 // p = 2^((s - m_ref) * scale * log2 e) rounded to bf16 in the B-operand layout of P V.  The row sum adds up the
@@ -275,12 +300,184 @@ __device__ __forceinline__ void exp_and_pack(const f32x16 (&sacc)[QB][2], bf16x8
     }
 }
 
+// ---- pieces of the pipelined loop, which advances in sub-tiles of 32 keys -------------------------------------
+// Source order below is the intended issue order: every MFMA group is followed by a slice of independent VALU
+// work, and the order is pinned with scheduling barriers, because one wave per SIMD has nobody else to fill its
+// MFMA latency.
+#if KSA_PIN
+#define KSA_STEP_FENCE() __builtin_amdgcn_sched_barrier(0)
+#else
+#define KSA_STEP_FENCE()
+#endif
+
+#ifdef KSA_DBG_NOLDS
+__device__ bf16x8 ksa_dbg_fake_init() { bf16x8 f; for (int e = 0; e < 8; ++e) f[e] = (__bf16)0.01f; return f; }
+#define ksa_dbg_fake ksa_dbg_fake_init()
+#endif
+template <int D>
+__device__ __forceinline__ bf16x8 read_k_operand(const unsigned char *lds, int lk, int s) {
+#ifdef KSA_DBG_NOLDS
+    { bf16x8 f = ksa_dbg_fake; asm volatile("" : "+v"(f)); return f; }
+#endif
+    return *reinterpret_cast<const bf16x8 *>(lds + (lk ^ (s << 5)));
+}
+
+template <int D>
+__device__ __forceinline__ bf16x8 read_v_operand(const unsigned char *lds, int lv, int hf, int db) {
+#ifdef KSA_DBG_NOLDS
+    { bf16x8 f = ksa_dbg_fake; asm volatile("" : "+v"(f)); return f; }
+#endif
+    const int a0 = (lv ^ (db << 6)) + hf * 16 * (D * 2), a1 = a0 + 8 * (D * 2);
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a0));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a1));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// Scores of one 32-key block alone (pipeline fill).
+template <int D>
+__device__ __forceinline__ void qk_only(const unsigned char *lds, int k_off, const LaneLds &ll,
+                                        const bf16x8 (&qreg)[QB][Tile<D>::KS], f32x16 (&s_out)[QB]) {
+    using T = Tile<D>;
+    const int lk = ll.k + k_off;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int g = 0; g < 16; ++g) s_out[qb][g] = 0.f;
+#pragma unroll
+    for (int s = 0; s < T::KS; ++s) {
+        const bf16x8 ka = read_k_operand<D>(lds, lk, s);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], s_out[qb], 0, 0, 0);
+    }
+}
+
+// One instruction's worth (1 KiB per wave) of a tile load.
+template <int D>
+__device__ __forceinline__ void issue_tile_load_part(const __bf16 *gbase, int off_i, unsigned char *lds, int buf_off,
+                                                     int wave, int i) {
+    using T = Tile<D>;
+    lds_direct_load_16(gbase + off_i, lds + buf_off + (16 * wave + T::RPI * i) * (D * 2));
+}
+
+// What the synchronising sub-tile of a tile does besides its arithmetic: wait for this wave's pieces of the next
+// tile, meet the other waves, and request the tile after that.
+template <int D>
+struct TileSync {
+    const __bf16 *kg, *vg;          // global addresses of the first row of the tile to request
+    const LaneOffsets<D> *off;
+    int k_dst, v_dst;               // LDS buffer offsets it goes to
+    int wave;
+};
+
+// One sub-tile (32 keys) of the pipelined loop, written in issue order:
+//   phase 1  s_next = K[next block] Q^T (MFMA)   next to   p = exp2((s_cur - m_ref) * sl) (VALU)
+//   phase 2  O^T += V^T[this block] P^T (MFMA)   next to   row maxima of s_next (VALU)
+// The first K operands arrive in ka_pre (read during the previous sub-tile) and the ones of the following sub-tile
+// are read at the end of phase 2; the first V operands are read at the end of phase 1, so no phase starts with the
+// MFMA pipe waiting for LDS.  With SYNC the per-tile barrier and the loads of the tile after next sit inside
+// phase 2.  Returns true if some row of s_next exceeds its reference maximum by more than the threshold.
+template <int D, bool SYNC>
+__device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
+                                        f32x16 (&s_next)[QB], const f32x16 (&s_cur)[QB], bf16x8 (&ka_pre)[2], int k_off,
+                                        int v_off, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st, float sl,
+                                        float (&tmax)[QB], const TileSync<D> &sync) {
+    using T = Tile<D>;
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of phase 2
+    constexpr int EPS1 = QB * 16 / T::KS;         // score registers turned into weights per phase-1 step
+    constexpr int MAX_FIRST = 2;                  // phase-2 step at which s_next is certainly complete
+    constexpr int EPS2 = (QB * 16 + NSTEP - MAX_FIRST - 1) / (NSTEP - MAX_FIRST);
+    static_assert(EPS1 >= 2 && EPS1 % 2 == 0, "exponentials are taken in pairs");
+    static_assert(NSTEP >= 4 && T::KS >= 4, "pipeline needs a few steps per phase");
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const int lk = ll.k + k_off, lv = ll.v + v_off, lkn = ll.k + k_next_off;
+    float msl[QB], rsum[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        msl[qb] = st.m_ref[qb] * sl;
+        rsum[qb] = st.l_part[qb];
+#pragma unroll
+        for (int g = 0; g < 16; ++g) s_next[qb][g] = 0.f;
+    }
+    bf16x8 p[QB][2];
+    bf16x8 ka[T::KS], va[NSTEP];
+    ka[0] = ka_pre[0];
+    ka[1] = ka_pre[1];
+    // ---- phase 1 ----
+#pragma unroll
+    for (int s = 0; s < T::KS; ++s) {
+        if (s + 2 < T::KS) ka[s + 2] = read_k_operand<D>(lds, lk, s + 2);
+        if (s == T::KS - 2) va[0] = read_v_operand<D>(lds, lv, 0, 0);
+        if (s == T::KS - 1) va[1] = read_v_operand<D>(lds, lv, 1 / T::DB, 1 % T::DB);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[qb][s], s_next[qb], 0, 0, 0);
+#pragma unroll
+        for (int e = s * EPS1; e < (s + 1) * EPS1; e += 2) {
+            const int qb = e / 16, g = e % 16;
+#ifdef KSA_DBG_NOEXP
+            if (e > 0) { p[qb][g / 8][g % 8] = p[0][0][0]; p[qb][g / 8][g % 8 + 1] = p[0][0][1]; continue; }
+#endif
+            bf16x2 pk;
+            pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_cur[qb][g], sl, -msl[qb]));
+            pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_cur[qb][g + 1], sl, -msl[qb]));
+            rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
+            p[qb][g / 8][g % 8] = pk[0];
+            p[qb][g / 8][g % 8 + 1] = pk[1];
+        }
+        KSA_STEP_FENCE();
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) st.l_part[qb] = rsum[qb];
+    // ---- phase 2 ----
+    float mx[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) mx[qb] = -INFINITY;
+#pragma unroll
+    for (int x = 0; x < NSTEP; ++x) {
+        const int hf = x / T::DB, db = x % T::DB;
+        if (x + 2 < NSTEP) va[x + 2] = read_v_operand<D>(lds, lv, (x + 2) / T::DB, (x + 2) % T::DB);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[x], p[qb][hf], oacc[qb][db], 0, 0, 0);
+        if (SYNC) {
+            if (x == 1) {
+#ifndef KSA_DBG_NOBAR
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next tile have landed
+                __syncthreads();                      // ... and everyone's; nobody still reads the buffers loaded next
+#endif
+            }
+#ifndef KSA_DBG_NOLOAD
+            // the tile after next, one K and one V instruction per step
+            if (x >= 2 && x - 2 < T::NI) {
+                issue_tile_load_part<D>(sync.kg, sync.off->k[x - 2], lds, sync.k_dst, sync.wave, x - 2);
+                issue_tile_load_part<D>(sync.vg, sync.off->v[x - 2], lds, sync.v_dst, sync.wave, x - 2);
+            }
+#endif
+        }
+        if (x >= NSTEP - 2) ka_pre[x - (NSTEP - 2)] = read_k_operand<D>(lds, lkn, x - (NSTEP - 2));
+        if (x >= MAX_FIRST) {
+#pragma unroll
+            for (int e = (x - MAX_FIRST) * EPS2; e < (x - MAX_FIRST + 1) * EPS2 && e < QB * 16; ++e)
+                mx[e / 16] = fmaxf(mx[e / 16], s_next[e / 16][e % 16]);
+        }
+        KSA_STEP_FENCE();
+    }
+    bool raise = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        tmax[qb] = fmaxf(mx[qb], other_half(mx[qb]));
+        raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+    }
+    return __builtin_amdgcn_ballot_w64(raise) != 0;
+}
+
 template <int D>
 __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs a) {
     using T = Tile<D>;
-    // two K tiles and two V tiles, back to back: buffer selection is an immediate offset
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * T::BYTES];
-    constexpr int K0 = 0, V0 = 2 * T::BYTES;   // second buffers follow at + T::BYTES
+    // three K tiles, then three V tiles: the pipelined loop loads two tiles ahead with one barrier per tile
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[6 * T::BYTES];
+    constexpr int K0 = 0, V0 = 3 * T::BYTES;
 
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
@@ -375,59 +572,72 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         LaneOffsets<D> off;
         if (invariant) lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
 
-        if (!masked && invariant && n_tiles >= 3) {
+        if (!masked && invariant && n_tiles >= 2) {
+#ifdef KSA_DEBUG_SKIP_HOT
+            continue;
+#endif
             // ================= pipelined loop over a run of FULL tiles ==================================
-            // P V lags one tile behind the scores: in iteration t the exponentials of tile t (VALU) are issued next
-            // to the MFMAs of O += P(t-1) V(t-1), and the score MFMAs of tile t run while the VALU is idle.
-            // LDS: K(t) in k buffer t&1, V(t) in v buffer t&1; loads of K(t+1), V(t) are issued in iteration t.
+            // The loop advances in sub-tiles of 32 keys (2t and 2t+1 for the halves of LDS tile t); see subtile().
+            // The accumulators are only touched by VALU in the rare "raise the reference" block between sub-tiles.
+            // LDS tile t lives in buffer t % 3; tile t+2 is requested right after the one barrier of tile t.
             auto tile_base = [&](int t) { return (int64_t)aug_row(a, space, seg_begin + t * BN) * a.ks[1]; };
-            __syncthreads();   // earlier readers of the LDS buffers are done
+            constexpr int HALF = 32 * (D * 2);   // byte offset of the second 32-key block of a tile
+            __syncthreads();                     // earlier readers of the LDS buffers are done
             issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
-            bf16x8 p_prev[QB][2][2];
-            for (int t = 0; t < n_tiles; ++t) {
-                const int cur = (t & 1) * T::BYTES, oth = T::BYTES - cur;
-                __builtin_amdgcn_s_waitcnt(0);   // this wave's pieces of K(t), V(t-1) have landed
-                __syncthreads();                 // ... and everyone's; all waves are past iteration t-1
-                if (t + 1 < n_tiles) issue_tile_load<D>(kbase + tile_base(t + 1), off.k, lds, K0 + oth, wave);
-                issue_tile_load<D>(vbase + tile_base(t), off.v, lds, V0 + cur, wave);
-#if KSA_SB
-                __builtin_amdgcn_sched_barrier(0);
-#endif
-                f32x16 sacc[QB][2];
-                score_mfma<D>(lds, K0 + cur, ll, qreg, sacc);
-#if KSA_SB
-                __builtin_amdgcn_sched_barrier(0);
-#endif
-                float tmax[QB];
-                if (tile_max(sacc, st, sl, tmax)) {
-                    // rare: the accumulators must take P(t-1) V(t-1) before they are rescaled
-                    if (t > 0) pv_mfma<D>(lds, V0 + oth, ll, p_prev, oacc);
-                    raise_reference<D>(st, tmax, oacc, sl);
-                    exp_and_pack(sacc, p_prev, st, sl);
-                } else {
-                    bf16x8 p_new[QB][2][2];
-                    exp_and_pack(sacc, p_new, st, sl);
-                    pv_mfma<D>(lds, V0 + oth, ll, p_prev, oacc);
-                    // one score MFMA's worth of VALU work per P V MFMA
-#pragma unroll
-                    for (int x = 0; x < KSA_SGB * QB * 2 * 2 * T::DB; ++x) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // exp
-                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // VALU
-                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads
-                    }
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                            for (int hf = 0; hf < 2; ++hf) p_prev[qb][kb][hf] = p_new[qb][kb][hf];
-                }
-            }
-            // drain: P V of the last tile (V(n_tiles-1) sits in buffer (n_tiles-1)&1)
+            issue_tile_load<D>(vbase + tile_base(0), off.v, lds, V0, wave);
+            issue_tile_load<D>(kbase + tile_base(1), off.k, lds, K0 + T::BYTES, wave);
+            issue_tile_load<D>(vbase + tile_base(1), off.v, lds, V0 + T::BYTES, wave);
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
-            pv_mfma<D>(lds, V0 + ((n_tiles - 1) & 1) * T::BYTES, ll, p_prev, oacc);
+            f32x16 s_a[QB], s_b[QB];
+            float tmax[QB];
+            qk_only<D>(lds, K0, ll, qreg, s_a);
+            bool raise;
+            {
+                float mx[QB];
+                raise = false;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    mx[qb] = s_a[qb][0];
+#pragma unroll
+                    for (int g = 1; g < 16; ++g) mx[qb] = fmaxf(mx[qb], s_a[qb][g]);
+                    tmax[qb] = fmaxf(mx[qb], other_half(mx[qb]));
+                    raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+                }
+                raise = __builtin_amdgcn_ballot_w64(raise) != 0;
+            }
+            bf16x8 ka_pre[2];
+            ka_pre[0] = read_k_operand<D>(lds, ll.k + K0 + HALF, 0);
+            ka_pre[1] = read_k_operand<D>(lds, ll.k + K0 + HALF, 1);
+            int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
+            TileSync<D> sync;
+            sync.off = &off;
+            sync.wave = wave;
+            for (int t = 0; t < n_tiles; ++t) {
+                // The tile loads bypass the compiler's bookkeeping but share the hardware counter with everything it
+                // loads itself (register reloads from scratch around this loop).  An explicit vmcnt(0) here, where
+                // only the loads of tile t+1 are in flight and are about to be needed anyway, keeps it from placing
+                // its own wait further down, behind the requests for tile t+2.
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                // the tile after next; past the end of the run the last tile is requested again (into a free buffer)
+                const int64_t tb = tile_base(t + 2 < n_tiles ? t + 2 : n_tiles - 1);
+                sync.kg = kbase + tb;
+                sync.vg = vbase + tb;
+                sync.k_dst = K0 + b_ld;
+                sync.v_dst = V0 + b_ld;
+                // ---- sub-tile 2t: weights from s_a, next scores (second half of tile t) into s_b ----
+                if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                raise = subtile<D, true>(lds, ll, qreg, s_b, s_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, K0 + b_nxt, oacc, st,
+                                         sl, tmax, sync);
+                // ---- sub-tile 2t+1: weights from s_b, next scores (first half of tile t+1) into s_a ----
+                // (for the last tile those scores come from a buffer that holds no new tile and are never used)
+                if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                raise = subtile<D, false>(lds, ll, qreg, s_a, s_b, ka_pre, K0 + b_nxt, V0 + b_cur + HALF, K0 + b_nxt + HALF,
+                                          oacc, st, sl, tmax, sync) &&
+                        (t + 1 < n_tiles);
+                const int b_old = b_cur;
+                b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
+            }
             continue;
         }
 

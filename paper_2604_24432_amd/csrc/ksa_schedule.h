@@ -7,7 +7,7 @@
 // Heights of the tiles the schedule is cut into.  A query tile is KSA_Q_TILE consecutive rows of one
 // index space (compact text indices or compact summary ordinals); a key tile is KSA_K_TILE rows.
 #ifndef KSA_Q_TILE
-#define KSA_Q_TILE 128
+#define KSA_Q_TILE 256
 #endif
 #define KSA_K_TILE 64
 #define KSA_MAX_SEGMENTS 5
