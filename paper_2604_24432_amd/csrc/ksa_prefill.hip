@@ -369,29 +369,48 @@ struct TileSync {
     int wave;
 };
 
+// Score registers leave the MFMA accumulators (AGPRs) one at a time, each exactly once: a plain element access
+// makes the compiler copy the whole 16-register tuple in one burst right behind the MFMAs that produce it.
+// The caller guarantees the distance to the producing MFMA (hazard: 8-pass MFMA result read by VALU).
+__device__ __forceinline__ float read_acc(const f32x16 &acc, int g) {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[g]));
+    return x;
+}
+// v_max3_f32 without the NaN-quieting self-maxima that fmaxf expands to
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float x;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(x) : "v"(a), "v"(b), "v"(c));
+    return x;
+}
+
 // One sub-tile (32 keys) of the pipelined loop, written in issue order:
-//   phase 1  s_next = K[next block] Q^T (MFMA)   next to   p = exp2((s_cur - m_ref) * sl) (VALU)
-//   phase 2  O^T += V^T[this block] P^T (MFMA)   next to   row maxima of s_next (VALU)
-// The first K operands arrive in ka_pre (read during the previous sub-tile) and the ones of the following sub-tile
-// are read at the end of phase 2; the first V operands are read at the end of phase 1, so no phase starts with the
-// MFMA pipe waiting for LDS.  With SYNC the per-tile barrier and the loads of the tile after next sit inside
-// phase 2.  Returns true if some row of s_next exceeds its reference maximum by more than the threshold.
+//   phase 1  s_next = K[next block] Q^T (MFMA)   next to   first half of p = exp2((s_cur - m_ref) * sl) (VALU)
+//   phase 2  O^T += V^T[this block] P^T (MFMA)   next to   second half of p, then s_next read out + row maxima
+// s_cur / sv_next are the scores as plain VGPR values (QB x 16 per lane).  The first K operands arrive in ka_pre
+// (read during the previous sub-tile) and the ones of the following sub-tile are read at the end of phase 2; the
+// first V operands are read at the end of phase 1, so no phase starts with the MFMA pipe waiting for LDS.  With
+// SYNC the per-tile barrier and the loads of the tile after next sit inside phase 2.  Returns true if some row of
+// the next scores exceeds its reference maximum by more than the threshold.
 template <int D, bool SYNC>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
-                                        f32x16 (&s_next)[QB], const f32x16 (&s_cur)[QB], bf16x8 (&ka_pre)[2], int k_off,
-                                        int v_off, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st, float sl,
-                                        float (&tmax)[QB], const TileSync<D> &sync) {
+                                        float (&sv_next)[QB][16], const float (&sv_cur)[QB][16], bf16x8 (&ka_pre)[2],
+                                        int k_off, int v_off, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
+                                        RowState &st, float sl, float (&tmax)[QB], const TileSync<D> &sync) {
     using T = Tile<D>;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of phase 2
-    constexpr int EPS1 = QB * 16 / T::KS;         // score registers turned into weights per phase-1 step
-    constexpr int MAX_FIRST = 2;                  // phase-2 step at which s_next is certainly complete
-    constexpr int EPS2 = (QB * 16 + NSTEP - MAX_FIRST - 1) / (NSTEP - MAX_FIRST);
-    static_assert(EPS1 >= 2 && EPS1 % 2 == 0, "exponentials are taken in pairs");
-    static_assert(NSTEP >= 4 && T::KS >= 4, "pipeline needs a few steps per phase");
+    constexpr int NE = QB * 8;                    // score registers per half (hf) of the sub-tile
+    constexpr int NPAIR = NE / 2;                 // pairs of weights per half
+    constexpr int HSTEP = NSTEP / 2;              // phase-2 steps that still use the first half of p
+    constexpr int RD_FIRST = 2;                   // phase-2 step from which s_next may be read (4+ MFMAs later)
+    constexpr int RD_STEPS = NSTEP - 1 - RD_FIRST;
+    constexpr int RPS = (QB * 16 + RD_STEPS - 1) / RD_STEPS;   // score registers read out per step
+    static_assert(NSTEP >= 4 && T::KS >= 4 && RD_STEPS >= 1, "pipeline needs a few steps per phase");
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     const int lk = ll.k + k_off, lv = ll.v + v_off, lkn = ll.k + k_next_off;
     float msl[QB], rsum[QB];
+    f32x16 s_next[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         msl[qb] = st.m_ref[qb] * sl;
@@ -400,6 +419,21 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         for (int g = 0; g < 16; ++g) s_next[qb][g] = 0.f;
     }
     bf16x8 p[QB][2];
+    // weights e (0 .. NE-1) of half hf: query block e / 8, register 8 * hf + e % 8
+    auto make_pair = [&](int hf, int e) {
+        const int qb = e / 8, g = 8 * hf + e % 8;
+        bf16x2 pk;
+#ifdef KSA_DBG_NOEXP
+        pk[0] = (__bf16)sv_cur[qb][g];
+        pk[1] = (__bf16)sv_cur[qb][g + 1];
+#else
+        pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sv_cur[qb][g], sl, -msl[qb]));
+        pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sv_cur[qb][g + 1], sl, -msl[qb]));
+#endif
+        rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
+        p[qb][hf][e % 8] = pk[0];
+        p[qb][hf][e % 8 + 1] = pk[1];
+    };
     bf16x8 ka[T::KS], va[NSTEP];
     ka[0] = ka_pre[0];
     ka[1] = ka_pre[1];
@@ -413,22 +447,10 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         for (int qb = 0; qb < QB; ++qb)
             s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[qb][s], s_next[qb], 0, 0, 0);
 #pragma unroll
-        for (int e = s * EPS1; e < (s + 1) * EPS1; e += 2) {
-            const int qb = e / 16, g = e % 16;
-#ifdef KSA_DBG_NOEXP
-            if (e > 0) { p[qb][g / 8][g % 8] = p[0][0][0]; p[qb][g / 8][g % 8 + 1] = p[0][0][1]; continue; }
-#endif
-            bf16x2 pk;
-            pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_cur[qb][g], sl, -msl[qb]));
-            pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_cur[qb][g + 1], sl, -msl[qb]));
-            rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
-            p[qb][g / 8][g % 8] = pk[0];
-            p[qb][g / 8][g % 8 + 1] = pk[1];
-        }
+        for (int pi = 0; pi < NPAIR; ++pi)   // first half of the weights, spread evenly over the steps
+            if (pi * T::KS / NPAIR == s) make_pair(0, 2 * pi);
         KSA_STEP_FENCE();
     }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) st.l_part[qb] = rsum[qb];
     // ---- phase 2 ----
     float mx[QB];
 #pragma unroll
@@ -440,6 +462,9 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
             oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[x], p[qb][hf], oacc[qb][db], 0, 0, 0);
+#pragma unroll
+        for (int pi = 0; pi < NPAIR; ++pi)       // second half, needed from step HSTEP on
+            if (pi * HSTEP / NPAIR == x) make_pair(1, 2 * pi);
         if (SYNC) {
             if (x == 1) {
 #ifndef KSA_DBG_NOBAR
@@ -456,19 +481,26 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
 #endif
         }
         if (x >= NSTEP - 2) ka_pre[x - (NSTEP - 2)] = read_k_operand<D>(lds, lkn, x - (NSTEP - 2));
-        if (x >= MAX_FIRST) {
+        if (x >= RD_FIRST && x < RD_FIRST + RD_STEPS) {
 #pragma unroll
-            for (int e = (x - MAX_FIRST) * EPS2; e < (x - MAX_FIRST + 1) * EPS2 && e < QB * 16; ++e)
-                mx[e / 16] = fmaxf(mx[e / 16], s_next[e / 16][e % 16]);
+            for (int e = (x - RD_FIRST) * RPS; e < (x - RD_FIRST + 1) * RPS && e < QB * 16; e += 2) {
+                const int qb = e / 16, g = e % 16;
+                sv_next[qb][g] = read_acc(s_next[qb], g);
+                sv_next[qb][g + 1] = read_acc(s_next[qb], g + 1);
+                mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
+            }
+        }
+        if (x == NSTEP - 1) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) tmax[qb] = max3(mx[qb], mx[qb], other_half(mx[qb]));
         }
         KSA_STEP_FENCE();
     }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) st.l_part[qb] = rsum[qb];
     bool raise = false;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        tmax[qb] = fmaxf(mx[qb], other_half(mx[qb]));
-        raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
-    }
+    for (int qb = 0; qb < QB; ++qb) raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
     return __builtin_amdgcn_ballot_w64(raise) != 0;
 }
 
@@ -589,19 +621,26 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             issue_tile_load<D>(vbase + tile_base(1), off.v, lds, V0 + T::BYTES, wave);
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
-            f32x16 s_a[QB], s_b[QB];
+            float sv_a[QB][16], sv_b[QB][16];
             float tmax[QB];
-            qk_only<D>(lds, K0, ll, qreg, s_a);
-            bool raise;
+            bool raise = false;
             {
-                float mx[QB];
-                raise = false;
+                f32x16 s0[QB];
+                qk_only<D>(lds, K0, ll, qreg, s0);
+                // MFMA results must have landed before they are read.  The wait names the accumulators as operands:
+                // that is what orders it behind the MFMAs and in front of the reads.
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) asm volatile("s_nop 15\n\ts_nop 15" : "+a"(s0[qb]));
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
-                    mx[qb] = s_a[qb][0];
+                    float mx = -INFINITY;
 #pragma unroll
-                    for (int g = 1; g < 16; ++g) mx[qb] = fmaxf(mx[qb], s_a[qb][g]);
-                    tmax[qb] = fmaxf(mx[qb], other_half(mx[qb]));
+                    for (int g = 0; g < 16; g += 2) {
+                        sv_a[qb][g] = read_acc(s0[qb], g);
+                        sv_a[qb][g + 1] = read_acc(s0[qb], g + 1);
+                        mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
+                    }
+                    tmax[qb] = max3(mx, mx, other_half(mx));
                     raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
                 }
                 raise = __builtin_amdgcn_ballot_w64(raise) != 0;
@@ -625,14 +664,14 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 sync.vg = vbase + tb;
                 sync.k_dst = K0 + b_ld;
                 sync.v_dst = V0 + b_ld;
-                // ---- sub-tile 2t: weights from s_a, next scores (second half of tile t) into s_b ----
+                // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
                 if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, true>(lds, ll, qreg, s_b, s_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, K0 + b_nxt, oacc, st,
+                raise = subtile<D, true>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, K0 + b_nxt, oacc, st,
                                          sl, tmax, sync);
-                // ---- sub-tile 2t+1: weights from s_b, next scores (first half of tile t+1) into s_a ----
+                // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
                 // (for the last tile those scores come from a buffer that holds no new tile and are never used)
                 if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, false>(lds, ll, qreg, s_a, s_b, ka_pre, K0 + b_nxt, V0 + b_cur + HALF, K0 + b_nxt + HALF,
+                raise = subtile<D, false>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur + HALF, K0 + b_nxt + HALF,
                                           oacc, st, sl, tmax, sync) &&
                         (t + 1 < n_tiles);
                 const int b_old = b_cur;
