@@ -75,6 +75,7 @@ def main():
     q, k, v = synth.make_prefill_inputs(cfg, device="cuda")
     o = torch.empty_like(q)
     lse = torch.empty((cfg.batch, cfg.n_q_heads, cfg.aug_len), dtype=torch.float32, device="cuda")
+    pws = torch.empty(K.prefill_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
 
     # ---- decode on a 128K context --------------------------------------------------------------------
     dcfg = synth.CONFIGS["decode_128k"]
@@ -96,7 +97,7 @@ def main():
     vis_rows = int(rg[1] + rg[3] + rg[5])
 
     def prefill():
-        K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse)
+        K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=pws)
 
     def decode():
         K.ksa_decode_fwd(dp, dq, k_cache, v_cache, pos_t, o=do, lse=dlse, workspace=ws, n_splits=args.decode_splits)

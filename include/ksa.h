@@ -118,17 +118,28 @@ int ksa_layout_launch_order(const ksa_layout *layout, int64_t *n_entries, uint8_
 /* ---- prefill ------------------------------------------------------------------------------------ */
 
 /*
- * ksa_prefill_fwd: attention output of all L augmented rows (text and summary rows alike).
+ * Bytes of device scratch memory ksa_prefill_fwd needs for this layout (0 for a NULL layout): room for a
+ * key-major copy of V, batch * n_kv_heads * head_dim * (n_text + n_summary_tokens, each rounded up to 64) bf16.
+ */
+size_t ksa_prefill_workspace_bytes(const ksa_layout *layout);
+
+/*
+ * ksa_prefill_fwd: attention output of all L augmented rows (text and summary rows alike),
+ *   O = softmax(Q K^T * scale + M_KSA) V with the visibility of Eq. 3 over the sequence of Eq. 1.
  *   q [B, L, Hq, d], k and v [B, L, Hkv, d], o [B, L, Hq, d]: device, bf16, last dim contiguous;
  *   *_strides = {batch, row, head} strides in elements; NULL = contiguous in the order above.
  *   lse: device fp32 [B, Hq, L] contiguous, natural-log sum-exp of the scaled visible scores; may be NULL.
+ *   workspace: device memory, 16-byte aligned, at least ksa_prefill_workspace_bytes(layout) bytes, owned by the
+ *   caller; the call overwrites it (a first kernel re-lays V out key-major for the main kernel) and needs it
+ *   until the work enqueued on `stream` has finished.  Calls that share a workspace must be stream-ordered.
  *   stream: hipStream_t (NULL = default stream).
- * The kernel walks the layout's schedule: bf16 MFMA for Q K^T and P V, fp32 online softmax.
- * Errors: INVALID_ARG (null tensors, misaligned pointers: 16-byte alignment required), HIP.
+ * The main kernel walks the layout's schedule: bf16 MFMA for Q K^T and P V, fp32 online softmax.
+ * Errors: INVALID_ARG (null tensors or workspace, misaligned pointers: 16-byte alignment required),
+ * WORKSPACE_TOO_SMALL, HIP.
  */
 int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void *v, void *o, float *lse,
                     const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
-                    void *stream);
+                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- decode over the summary KV cache (section 2.3.1) ------------------------------------------ */
 

@@ -66,7 +66,8 @@ def lib():
         "ksa_layout_mask_row": (C.c_int, [vp, C.c_int64, vp]),
         "ksa_layout_tile_pairs": (C.c_int, [vp, i64p, vp, vp, vp, vp, vp, vp, vp]),
         "ksa_layout_launch_order": (C.c_int, [vp, i64p, vp, vp, vp, vp]),
-        "ksa_prefill_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64p, i64p, i64p, vp]),
+        "ksa_prefill_workspace_bytes": (C.c_size_t, [vp]),
+        "ksa_prefill_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64p, i64p, i64p, vp, C.c_size_t, vp]),
         "ksa_cache_geometry": (C.c_int, [pp, i32p, i32p]),
         "ksa_cache_text_row": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_cache_summary_row": (C.c_int, [pp, C.c_int64, i32p]),
@@ -85,7 +86,7 @@ def lib():
 
 EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload", "ksa_layout_dims",
                     "ksa_layout_index_maps", "ksa_layout_row_ranges", "ksa_layout_mask_row",
-                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_fwd", "ksa_cache_geometry", "ksa_cache_text_row",
+                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_cache_geometry", "ksa_cache_text_row",
                     "ksa_cache_summary_row", "ksa_decode_ranges", "ksa_decode_workspace_bytes",
                     "ksa_decode_fwd", "ksa_status_string", "ksa_build_info")
 
@@ -198,8 +199,13 @@ def _require(t, name, dtype, ndim):
         raise ValueError(f"{name}: expected {ndim}-d {dtype} with contiguous last dim, got {t.dtype} {tuple(t.shape)}")
 
 
-def ksa_prefill_fwd(layout: Layout, q, k, v, o=None, lse=None, return_lse=True, stream=None):
-    """q [B, L, Hq, d], k/v [B, L, Hkv, d] bf16 on the GPU -> o [B, L, Hq, d] bf16, lse [B, Hq, L] fp32."""
+def prefill_workspace_bytes(layout: Layout) -> int:
+    return int(lib().ksa_prefill_workspace_bytes(layout.handle))
+
+
+def ksa_prefill_fwd(layout: Layout, q, k, v, o=None, lse=None, return_lse=True, workspace=None, stream=None):
+    """q [B, L, Hq, d], k/v [B, L, Hkv, d] bf16 on the GPU -> o [B, L, Hq, d] bf16, lse [B, Hq, L] fp32.
+    workspace: uint8 GPU tensor of at least prefill_workspace_bytes(layout) bytes (allocated here if omitted)."""
     import torch
     p = layout.params
     for t, name in ((q, "q"), (k, "k"), (v, "v")):
@@ -214,10 +220,14 @@ def ksa_prefill_fwd(layout: Layout, q, k, v, o=None, lse=None, return_lse=True, 
     if lse is None and return_lse:
         lse = torch.empty((p.batch, p.n_q_heads, layout.aug_len), dtype=torch.float32, device=q.device)
     lse_ptr = C.c_void_p(lse.data_ptr()) if lse is not None else None
+    if workspace is None:
+        workspace = torch.empty(prefill_workspace_bytes(layout), dtype=torch.uint8, device=q.device)
+    if not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 GPU tensor")
     rc = lib().ksa_prefill_fwd(layout.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
                                C.c_void_p(v.data_ptr()), C.c_void_p(o.data_ptr()), lse_ptr,
                                _strides3(q, (0, 1, 2)), _strides3(k, (0, 1, 2)), _strides3(o, (0, 1, 2)),
-                               _stream_ptr(stream))
+                               C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream))
     _check(rc, "ksa_prefill_fwd")
     return o, lse
 

@@ -66,10 +66,14 @@ int ksa_layout_upload(ksa_layout *lay) {
     return KSA_OK;
 }
 
+size_t ksa_prefill_workspace_bytes(const ksa_layout *lay) { return lay ? ksa_prefill_workspace_size(lay->p) : 0; }
+
 int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v, void *o, float *lse,
                     const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
-                    void *stream) {
-    if (!lay || !q || !k || !v || !o) return KSA_ERR_INVALID_ARG;
+                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (!lay || !q || !k || !v || !o || !workspace) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return KSA_ERR_INVALID_ARG;
+    if (workspace_bytes < ksa_prefill_workspace_size(lay->p)) return KSA_ERR_WORKSPACE_TOO_SMALL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return KSA_ERR_INVALID_ARG;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return KSA_ERR_INVALID_ARG;
     const ksa_params &p = lay->p;
@@ -86,6 +90,8 @@ int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v
     a.n_entries = (int32_t)lay->entries.size();
     a.p = p;
     a.aug_len = lay->aug_len;
+    a.workspace = workspace;
+    a.workspace_bytes = workspace_bytes;
     return ksa_launch_prefill(a, stream);
 }
 

@@ -33,7 +33,10 @@ struct KsaPrefillLaunch {
     int32_t n_entries;
     ksa_params p;
     int64_t aug_len;
+    void *workspace;          // key-major copy of V, written by the launch itself
+    size_t workspace_bytes;
 };
+size_t ksa_prefill_workspace_size(const ksa_params &p);
 int ksa_launch_prefill(const KsaPrefillLaunch &a, void *stream);
 
 struct KsaDecodeLaunch {

@@ -42,24 +42,42 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
 #define GLOBAL_PTR(T) __attribute__((address_space(1))) T *
 
-#ifndef KSA_SB
-#define KSA_SB 1
-#endif
 #ifndef KSA_PIN
 #define KSA_PIN 1
 #endif
-constexpr int NW = 4;                         // waves per workgroup
+#ifndef KSA_NW
+#define KSA_NW 4
+#endif
+constexpr int NW = KSA_NW;                    // waves per workgroup
+constexpr int RW = KSA_K_TILE / NW;           // rows of a key tile each wave fetches
 constexpr int BN = KSA_K_TILE;                // keys per tile
 constexpr int QB = KSA_Q_TILE / (NW * 32);    // 32-row query blocks per wave
 static_assert(KSA_Q_TILE == NW * QB * 32, "query tile must be a whole number of 32-row blocks per wave");
 static_assert(BN == 64, "key tile is two 32-key MFMA blocks");
 constexpr float RESCALE_THRESHOLD_LOG2 = 8.0f;   // raise the running max only for a jump above 2^8
 
+#ifdef KSA_TRACE
+// development only: cycle counts of the pieces of the pipelined loop, summed over every wave
+__device__ unsigned long long ksa_trace_buf[16];
+struct Trace { unsigned long long acc[16]; };
+#define KSA_NOW() __builtin_readcyclecounter()
+#define KSA_TRACE_ARG , Trace &tr
+#define KSA_TRACE_PASS , tr
+#else
+#define KSA_TRACE_ARG
+#define KSA_TRACE_PASS
+#endif
+
 struct PrefillArgs {
     const __bf16 *q, *k, *v;
     __bf16 *o;
     float *lse;
     int64_t qs[3], ks[3], os[3];   // {batch, row, head} strides in elements
+    const __bf16 *vt;              // key-major copy of V per index space (see ksa_vt_kernel)
+    int64_t vt_sum_off;            // element offset of the summary-space part of vt
+    int32_t nt_pad, ns_pad;        // row lengths (keys) of the text / summary parts
+    int32_t n_text, n_sum;         // keys per index space
+    int32_t n_kv_heads;
     const KsaWorkItem *items;
     const KsaWgEntry *entries;
     int32_t c, m, C, w;            // chunk_len, n_summary, window_chunks, c + m
@@ -99,7 +117,11 @@ template <int D>
 struct Tile {
     static constexpr int CH = D / 8;           // 16-byte chunks per row
     static constexpr int RPI = 64 / CH;        // rows covered by one wavefront load instruction
-    static constexpr int NI = 16 / RPI;        // load instructions per wave per tile (16 rows per wave)
+    static constexpr int NI = RW / RPI;        // load instructions per wave per tile (RW rows per wave)
+    static_assert(RW % RPI == 0 && NI >= 1, "a wave's share of a tile is a whole number of load instructions");
+    static constexpr int VROWS = D / NW;       // head-dim rows of a key-major V tile each wave fetches (128 bytes each)
+    static constexpr int NIV = VROWS / 8;      // load instructions per wave for it
+    static_assert(VROWS % 8 == 0 && NIV >= 1, "a wave's share of a key-major V tile is a whole number of load instructions");
     static constexpr int KS = D / 16;          // k steps of the score MFMA
     static constexpr int DB = D / 32;          // 32-column blocks of the output
     static constexpr int BYTES = BN * D * 2;
@@ -109,6 +131,7 @@ struct Tile {
 template <int D>
 struct LaneOffsets {
     int k[Tile<D>::NI], v[Tile<D>::NI];
+    int vt[Tile<D>::NIV];   // key-major V: offsets relative to (row 0 of the head, first key of the tile)
 };
 
 // Offsets for the tile whose first key is kt; rows beyond `last` (inclusive bound) are clamped to it.
@@ -118,13 +141,28 @@ __device__ __forceinline__ void lane_offsets(const PrefillArgs &a, int space, in
     using T = Tile<D>;
 #pragma unroll
     for (int i = 0; i < T::NI; ++i) {
-        const int row = 16 * wave + T::RPI * i + lane / T::CH;
+        const int row = RW * wave + T::RPI * i + lane / T::CH;
         const int pch = lane % T::CH;
         int kc = kt + row;
         kc = kc < last ? kc : last;
         const int rel = (aug_row(a, space, kc) - base_aug) * (int)a.ks[1];
         off.k[i] = rel + ((pch ^ k_swz<D>(row)) << 3);
         off.v[i] = rel + ((pch ^ v_swz<D>(row)) << 3);
+    }
+}
+
+// Key-major V tile in LDS: [D head-dim rows][8 pieces of 16 bytes]; a piece holds the eight keys one lane feeds to
+// one P V MFMA.  The piece index is XORed with (row >> 1) & 7, which makes the 16 lanes of a ds_read_b128 phase hit
+// 16 different 16-byte bank groups.
+__device__ __forceinline__ int vt_swz(int d_row) { return (d_row >> 1) & 7; }
+
+template <int D>
+__device__ __forceinline__ void lane_offsets_vt(int vt_stride, int wave, int lane, LaneOffsets<D> &off) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int i = 0; i < T::NIV; ++i) {
+        const int d_row = T::VROWS * wave + 8 * i + (lane >> 3);
+        off.vt[i] = d_row * vt_stride + (((lane & 7) ^ vt_swz(d_row)) << 3);
     }
 }
 
@@ -145,7 +183,7 @@ __device__ __forceinline__ void issue_tile_load(const __bf16 *gbase, const int (
     using T = Tile<D>;
 #pragma unroll
     for (int i = 0; i < T::NI; ++i) {
-        lds_direct_load_16(gbase + off[i], lds + buf_off + (16 * wave + T::RPI * i) * (D * 2));
+        lds_direct_load_16(gbase + off[i], lds + buf_off + (RW * wave + T::RPI * i) * (D * 2));
     }
 }
 
@@ -154,6 +192,8 @@ __device__ __forceinline__ void issue_tile_load(const __bf16 *gbase, const int (
 struct LaneLds {
     int k;   // K operand: row r, chunk (swizzle(r) ^ h); XOR (s << 5) selects k step s
     int v;   // V^T operand: this lane's address row / column of the transposing read; XOR (db << 6) selects the column block
+    int vt;  // V^T operand out of a key-major tile: row r, piece (swizzle(r) ^ h); XOR ((2 * sb + hf) << 5) selects the
+             // 16-key group, + db * 4096 the block of 32 head-dim rows
 };
 
 template <int D>
@@ -167,6 +207,7 @@ __device__ __forceinline__ LaneLds lane_lds(int lane) {
     LaneLds L;
     L.k = r * (D * 2) + ((k_swz<D>(r) ^ h) << 4);
     L.v = t_row * (D * 2) + (((t_col >> 3) ^ v_swz<D>(t_row)) << 4) + ((t_col & 7) << 1);
+    L.vt = r * 128 + ((h ^ vt_swz(r)) << 4);
     return L;
 }
 
@@ -310,27 +351,36 @@ __device__ __forceinline__ void exp_and_pack(const f32x16 (&sacc)[QB][2], bf16x8
 #define KSA_STEP_FENCE()
 #endif
 
-#ifdef KSA_DBG_NOLDS
-__device__ bf16x8 ksa_dbg_fake_init() { bf16x8 f; for (int e = 0; e < 8; ++e) f[e] = (__bf16)0.01f; return f; }
-#define ksa_dbg_fake ksa_dbg_fake_init()
-#endif
 template <int D>
 __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char *lds, int lk, int s) {
-#ifdef KSA_DBG_NOLDS
-    { bf16x8 f = ksa_dbg_fake; asm volatile("" : "+v"(f)); return f; }
-#endif
     return *reinterpret_cast<const bf16x8 *>(lds + (lk ^ (s << 5)));
 }
 
 template <int D>
 __device__ __forceinline__ bf16x8 read_v_operand(const unsigned char *lds, int lv, int hf, int db) {
-#ifdef KSA_DBG_NOLDS
-    { bf16x8 f = ksa_dbg_fake; asm volatile("" : "+v"(f)); return f; }
-#endif
     const int a0 = (lv ^ (db << 6)) + hf * 16 * (D * 2), a1 = a0 + 8 * (D * 2);
     const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a0));
     const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a1));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// V^T operand (32 head-dim rows x 16 keys) out of a key-major tile: one 16-byte read per lane
+__device__ __forceinline__ bf16x8 read_vt_operand(const unsigned char *lds, int lvt, int hf, int db) {
+    return *reinterpret_cast<const bf16x8 *>(lds + ((lvt ^ (hf << 5)) + db * 4096));
+}
+
+// Score MFMA with its result in ordinary VGPRs.  The scores are consumed by VALU code (exp2, max); the compiler
+// places MFMA results in accumulation registers, and every v_accvgpr_read of one of them while other MFMAs are in
+// flight was measured to cost about as much as an exponential.  Written as inline assembly, the instruction's
+// register classes are ours to choose: result VGPRs, K operand VGPRs (fresh from LDS), Q operand accumulation
+// registers (resident for the whole kernel, never touched by VALU).
+// The compiler does not know that these statements are MFMAs, so it inserts none of the wait states an MFMA result
+// needs before VALU code may read it: callers keep every read at least two later MFMAs away.
+__device__ __forceinline__ void score_mfma_first(f32x16 &acc, const bf16x8 &k_op, const bf16x8 &q_op) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_op), "a"(q_op));
+}
+__device__ __forceinline__ void score_mfma_next(f32x16 &acc, const bf16x8 &k_op, const bf16x8 &q_op) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_op), "a"(q_op));
 }
 
 // Scores of one 32-key block alone (pipeline fill).
@@ -340,14 +390,15 @@ __device__ __forceinline__ void qk_only(const unsigned char *lds, int k_off, con
     using T = Tile<D>;
     const int lk = ll.k + k_off;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int g = 0; g < 16; ++g) s_out[qb][g] = 0.f;
-#pragma unroll
     for (int s = 0; s < T::KS; ++s) {
         const bf16x8 ka = read_k_operand<D>(lds, lk, s);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], s_out[qb], 0, 0, 0);
+        for (int qb = 0; qb < QB; ++qb) {
+            if (s == 0)
+                score_mfma_first(s_out[qb], ka, qreg[qb][s]);
+            else
+                score_mfma_next(s_out[qb], ka, qreg[qb][s]);
+        }
     }
 }
 
@@ -356,7 +407,14 @@ template <int D>
 __device__ __forceinline__ void issue_tile_load_part(const __bf16 *gbase, int off_i, unsigned char *lds, int buf_off,
                                                      int wave, int i) {
     using T = Tile<D>;
-    lds_direct_load_16(gbase + off_i, lds + buf_off + (16 * wave + T::RPI * i) * (D * 2));
+    lds_direct_load_16(gbase + off_i, lds + buf_off + (RW * wave + T::RPI * i) * (D * 2));
+}
+
+template <int D>
+__device__ __forceinline__ void issue_vt_load_part(const __bf16 *gbase, int off_i, unsigned char *lds, int buf_off, int wave,
+                                                   int i) {
+    using T = Tile<D>;
+    lds_direct_load_16(gbase + off_i, lds + buf_off + (T::VROWS * wave + 8 * i) * 128);
 }
 
 // What the synchronising sub-tile of a tile does besides its arithmetic: wait for this wave's pieces of the next
@@ -369,14 +427,6 @@ struct TileSync {
     int wave;
 };
 
-// Score registers leave the MFMA accumulators (AGPRs) one at a time, each exactly once: a plain element access
-// makes the compiler copy the whole 16-register tuple in one burst right behind the MFMAs that produce it.
-// The caller guarantees the distance to the producing MFMA (hazard: 8-pass MFMA result read by VALU).
-__device__ __forceinline__ float read_acc(const f32x16 &acc, int g) {
-    float x;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[g]));
-    return x;
-}
 // v_max3_f32 without the NaN-quieting self-maxima that fmaxf expands to
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float x;
@@ -384,118 +434,169 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return x;
 }
 
-// One sub-tile (32 keys) of the pipelined loop, written in issue order:
-//   phase 1  s_next = K[next block] Q^T (MFMA)   next to   first half of p = exp2((s_cur - m_ref) * sl) (VALU)
-//   phase 2  O^T += V^T[this block] P^T (MFMA)   next to   second half of p, then s_next read out + row maxima
-// s_cur / sv_next are the scores as plain VGPR values (QB x 16 per lane).  The first K operands arrive in ka_pre
-// (read during the previous sub-tile) and the ones of the following sub-tile are read at the end of phase 2; the
-// first V operands are read at the end of phase 1, so no phase starts with the MFMA pipe waiting for LDS.  With
-// SYNC the per-tile barrier and the loads of the tile after next sit inside phase 2.  Returns true if some row of
-// the next scores exceeds its reference maximum by more than the threshold.
+// One sub-tile (32 keys) of the pipelined loop, written in issue order as a sequence of slots.  A slot is one MFMA
+// plus a slice of independent VALU work and ends with a scheduling fence: a wave issues in order, so VALU work that
+// is not placed between two MFMAs is not overlapped with anything.
+//   slots 0 .. KS*QB-1          s_next = K[next block] Q^T
+//   slots KS*QB .. 2*KS*QB-1    O^T += V^T[this block] P^T
+//   VALU stream, spread over the slots in this order:
+//     E(e)  weight of score e of the current block, p = exp2((s_cur - m_ref) * sl); every second one packs a pair to
+//           bf16 and adds it to the row sum.  First the 16-key half the first P V slots need, then the other half.
+//     R(j)  two scores of s_next leave the accumulators (at least four MFMAs behind the last score MFMA), row max
+// s_cur / sv_next are the scores as plain VGPR values (QB x 16 per lane).  The K operands of this sub-tile arrive in
+// ka (read from LDS during the previous sub-tile), the ones of the following sub-tile are read during the P V slots,
+// and the V operands during the score slots: every LDS read is issued a whole phase before its first use.  With SYNC
+// the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true if
+// some row of the next scores exceeds its reference maximum by more than the threshold.
 template <int D, bool SYNC>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
-                                        float (&sv_next)[QB][16], const float (&sv_cur)[QB][16], bf16x8 (&ka_pre)[2],
-                                        int k_off, int v_off, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
-                                        RowState &st, float sl, float (&tmax)[QB], const TileSync<D> &sync) {
+                                        f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::KS],
+                                        int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st, float sl,
+                                        float (&tmax)[QB], const TileSync<D> &sync KSA_TRACE_ARG) {
     using T = Tile<D>;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of phase 2
-    constexpr int NE = QB * 8;                    // score registers per half (hf) of the sub-tile
-    constexpr int NPAIR = NE / 2;                 // pairs of weights per half
-    constexpr int HSTEP = NSTEP / 2;              // phase-2 steps that still use the first half of p
-    constexpr int RD_FIRST = 2;                   // phase-2 step from which s_next may be read (4+ MFMAs later)
-    constexpr int RD_STEPS = NSTEP - 1 - RD_FIRST;
-    constexpr int RPS = (QB * 16 + RD_STEPS - 1) / RD_STEPS;   // score registers read out per step
-    static_assert(NSTEP >= 4 && T::KS >= 4 && RD_STEPS >= 1, "pipeline needs a few steps per phase");
+    constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of the P V phase
+    static_assert(NSTEP == T::KS, "one V operand is fetched per score step");
+    constexpr int N1 = T::KS * QB;                // score slots
+    constexpr int N2 = NSTEP * QB;                // P V slots
+    constexpr int NE = QB * 16;                   // weights per lane
+    // The VALU stream is software-pipelined over the slots: a wave issues in order, a dependent VALU instruction
+    // waits several cycles for its operand and a transcendental result some more, so the three stages of a weight
+    //   F  x = s * sl - m_ref * sl        X  w = exp2(x)        C  pack a pair to bf16, add it to the row sum
+    // run in three consecutive slots, and a read-out unit takes its row maximum one slot after its two reads.
+    constexpr int E_SLOTS = N1 + N2 / 2 - 2;      // slots that start a weight; the last C stage ends before slot N1 + N2 / 2
+    constexpr int R_FIRST = N1 + (N2 >= 8 ? 4 : 2);   // first slot that may read s_next (its last MFMA is two or more MFMAs back)
+    constexpr int R_SLOTS = N1 + N2 - 1 - R_FIRST;
+    constexpr int NR = QB * 8;                    // read-out units (two scores each)
+    static_assert(E_SLOTS >= 1 && R_SLOTS >= 1, "the phases are too short for the pipelined VALU stream");
+    static_assert(1 + T::NI + T::NIV <= N2, "the tile requests do not fit into the P V slots");
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    const int lk = ll.k + k_off, lv = ll.v + v_off, lkn = ll.k + k_next_off;
-    float msl[QB], rsum[QB];
-    f32x16 s_next[QB];
+    const int lv = (ll.vt ^ (sb << 6)) + v_off, lkn = ll.k + k_next_off;
+    float msl[QB], rsum[QB], mx[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         msl[qb] = st.m_ref[qb] * sl;
         rsum[qb] = st.l_part[qb];
-#pragma unroll
-        for (int g = 0; g < 16; ++g) s_next[qb][g] = 0.f;
+        mx[qb] = -INFINITY;
     }
     bf16x8 p[QB][2];
-    // weights e (0 .. NE-1) of half hf: query block e / 8, register 8 * hf + e % 8
-    auto make_pair = [&](int hf, int e) {
-        const int qb = e / 8, g = 8 * hf + e % 8;
-        bf16x2 pk;
-#ifdef KSA_DBG_NOEXP
-        pk[0] = (__bf16)sv_cur[qb][g];
-        pk[1] = (__bf16)sv_cur[qb][g + 1];
+    bf16x8 va[NSTEP];
+    float xs[NE], ws[NE];
+    // weight e = hf * (QB * 8) + qb * 8 + i  ->  score register 8 * hf + i of query block qb;
+    // first the 16-key half (hf = 0) that the first P V slots need
+    auto slot_of_e = [](int e) { return e * E_SLOTS / NE; };
+    auto slot_of_r = [](int j) { return R_FIRST + j * R_SLOTS / NR; };
+    auto valu_slice = [&](int u) {
+#if defined(KSA_ABL) && (KSA_ABL & 1)
+        if (u == 0) { for (int q2 = 0; q2 < QB; ++q2) for (int h2 = 0; h2 < 2; ++h2) for (int i2 = 0; i2 < 8; ++i2) p[q2][h2][i2] = (__bf16)0.5f; }
+        return;
+#endif
+#if defined(KSA_ABL) && (KSA_ABL & 16)
+        if (u == 0) { for (int q2 = 0; q2 < QB; ++q2) for (int h2 = 0; h2 < 2; ++h2) for (int i2 = 0; i2 < 8; ++i2) p[q2][h2][i2] = (__bf16)0.5f; }
 #else
-        pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sv_cur[qb][g], sl, -msl[qb]));
-        pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sv_cur[qb][g + 1], sl, -msl[qb]));
-#endif
-        rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
-        p[qb][hf][e % 8] = pk[0];
-        p[qb][hf][e % 8 + 1] = pk[1];
-    };
-    bf16x8 ka[T::KS], va[NSTEP];
-    ka[0] = ka_pre[0];
-    ka[1] = ka_pre[1];
-    // ---- phase 1 ----
 #pragma unroll
-    for (int s = 0; s < T::KS; ++s) {
-        if (s + 2 < T::KS) ka[s + 2] = read_k_operand<D>(lds, lk, s + 2);
-        if (s == T::KS - 2) va[0] = read_v_operand<D>(lds, lv, 0, 0);
-        if (s == T::KS - 1) va[1] = read_v_operand<D>(lds, lv, 1 / T::DB, 1 % T::DB);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[qb][s], s_next[qb], 0, 0, 0);
-#pragma unroll
-        for (int pi = 0; pi < NPAIR; ++pi)   // first half of the weights, spread evenly over the steps
-            if (pi * T::KS / NPAIR == s) make_pair(0, 2 * pi);
-        KSA_STEP_FENCE();
-    }
-    // ---- phase 2 ----
-    float mx[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) mx[qb] = -INFINITY;
-#pragma unroll
-    for (int x = 0; x < NSTEP; ++x) {
-        const int hf = x / T::DB, db = x % T::DB;
-        if (x + 2 < NSTEP) va[x + 2] = read_v_operand<D>(lds, lv, (x + 2) / T::DB, (x + 2) % T::DB);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[x], p[qb][hf], oacc[qb][db], 0, 0, 0);
-#pragma unroll
-        for (int pi = 0; pi < NPAIR; ++pi)       // second half, needed from step HSTEP on
-            if (pi * HSTEP / NPAIR == x) make_pair(1, 2 * pi);
-        if (SYNC) {
-            if (x == 1) {
-#ifndef KSA_DBG_NOBAR
-                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next tile have landed
-                __syncthreads();                      // ... and everyone's; nobody still reads the buffers loaded next
-#endif
+        for (int e = 1; e < NE; e += 2)
+            if (slot_of_e(e) + 2 == u) {   // C
+                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
+                bf16x2 pk;
+                pk[0] = (__bf16)ws[e - 1];
+                pk[1] = (__bf16)ws[e];
+                rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
+                asm volatile("" : "+v"(rsum[qb]));   // keeps the sum in this slot instead of at the end of the block
+                p[qb][hf][i - 1] = pk[0];
+                p[qb][hf][i] = pk[1];
             }
-#ifndef KSA_DBG_NOLOAD
-            // the tile after next, one K and one V instruction per step
-            if (x >= 2 && x - 2 < T::NI) {
-                issue_tile_load_part<D>(sync.kg, sync.off->k[x - 2], lds, sync.k_dst, sync.wave, x - 2);
-                issue_tile_load_part<D>(sync.vg, sync.off->v[x - 2], lds, sync.v_dst, sync.wave, x - 2);
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+            if (slot_of_e(e | 1) + 1 == u) {   // X (both weights of a pair in the slot of the odd one)
+                ws[e] = __builtin_amdgcn_exp2f(xs[e]);
+                asm volatile("" : "+v"(ws[e]));
+            }
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+            if (slot_of_e(e | 1) == u) {   // F
+                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
+                xs[e] = fmaf(sv_cur[qb][8 * hf + i], sl, -msl[qb]);
+                asm volatile("" : "+v"(xs[e]));
             }
 #endif
-        }
-        if (x >= NSTEP - 2) ka_pre[x - (NSTEP - 2)] = read_k_operand<D>(lds, lkn, x - (NSTEP - 2));
-        if (x >= RD_FIRST && x < RD_FIRST + RD_STEPS) {
+#if !(defined(KSA_ABL) && (KSA_ABL & 8))
 #pragma unroll
-            for (int e = (x - RD_FIRST) * RPS; e < (x - RD_FIRST + 1) * RPS && e < QB * 16; e += 2) {
-                const int qb = e / 16, g = e % 16;
-                sv_next[qb][g] = read_acc(s_next[qb], g);
-                sv_next[qb][g + 1] = read_acc(s_next[qb], g + 1);
+        for (int j = 0; j < NR; ++j)
+            if (slot_of_r(j) == u) {
+                const int qb = j / 8, g = 2 * (j % 8);
                 mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
             }
-        }
-        if (x == NSTEP - 1) {
+#endif
+    };
+#ifdef KSA_TRACE
+    const unsigned long long T0 = KSA_NOW();
+    unsigned long long T3 = 0;
+#endif
+    // ---- score slots ----
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) tmax[qb] = max3(mx[qb], mx[qb], other_half(mx[qb]));
+    for (int u = 0; u < N1; ++u) {
+        const int sk = u / QB, qb = u % QB;
+#if defined(KSA_ABL) && (KSA_ABL & 2)
+        if (qb == 0) va[sk] = ka[sk];
+#else
+        if (qb == 0) va[sk] = read_vt_operand(lds, lv, sk / T::DB, sk % T::DB);   // needed a whole phase from now
+#endif
+        if (sk == 0)
+            score_mfma_first(sv_next[qb], ka[sk], qreg[qb][sk]);
+        else
+            score_mfma_next(sv_next[qb], ka[sk], qreg[qb][sk]);
+        valu_slice(u);
+        KSA_STEP_FENCE();
+    }
+#ifdef KSA_TRACE
+    const unsigned long long T1 = KSA_NOW();
+    tr.acc[SYNC ? 0 : 4] += T1 - T0;
+    T3 = T1;
+#endif
+    // ---- P V slots ----
+#pragma unroll
+    for (int u = 0; u < N2; ++u) {
+        const int x = u / QB, qb = u % QB;
+        const int hf = x / T::DB, db = x % T::DB;
+        oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[x], p[qb][hf], oacc[qb][db], 0, 0, 0);
+        if (SYNC) {
+            if (u == 0) {
+#ifdef KSA_TRACE
+                const unsigned long long T2 = KSA_NOW();
+#endif
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next tile have landed
+#ifdef KSA_TRACE
+                const unsigned long long T2b = KSA_NOW();
+                tr.acc[1] += T2b - T2;
+#endif
+                __syncthreads();                      // ... and everyone's; nobody still reads the buffers loaded next
+#ifdef KSA_TRACE
+                T3 = KSA_NOW();
+                tr.acc[2] += T3 - T2b;
+#endif
+            }
+            // the tile after next, one instruction per slot
+#if !(defined(KSA_ABL) && (KSA_ABL & 4))
+            if (u >= 1 && u - 1 < T::NI)
+                issue_tile_load_part<D>(sync.kg, sync.off->k[u - 1], lds, sync.k_dst, sync.wave, u - 1);
+            if (u >= 1 + T::NI && u - 1 - T::NI < T::NIV)
+                issue_vt_load_part<D>(sync.vg, sync.off->vt[u - 1 - T::NI], lds, sync.v_dst, sync.wave, u - 1 - T::NI);
+#endif
+        }
+#if !(defined(KSA_ABL) && (KSA_ABL & 2))
+        if (qb == QB - 1) ka[x] = read_k_operand<D>(lds, lkn, x);   // K operands of the following sub-tile
+#endif
+        valu_slice(N1 + u);
+        if (u == N2 - 1) {
+#pragma unroll
+            for (int q2 = 0; q2 < QB; ++q2) tmax[q2] = max3(mx[q2], mx[q2], other_half(mx[q2]));
         }
         KSA_STEP_FENCE();
     }
+#ifdef KSA_TRACE
+    tr.acc[SYNC ? 3 : 5] += KSA_NOW() - T3;
+#endif
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) st.l_part[qb] = rsum[qb];
     bool raise = false;
@@ -511,6 +612,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[6 * T::BYTES];
     constexpr int K0 = 0, V0 = 3 * T::BYTES;
 
+#ifdef KSA_TRACE
+    Trace tr;
+    for (int i = 0; i < 16; ++i) tr.acc[i] = 0;
+    const unsigned long long TK0 = KSA_NOW();
+    const unsigned long long TW0 = wall_clock64();
+#endif
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
@@ -559,6 +666,9 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16);
             else
                 qreg[qb][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            // From here on the Q operand is a value of the accumulation-register class: the score MFMAs name it as
+            // such, and without this the compiler re-copies it in front of every one of them.
+            asm volatile("" : "+a"(qreg[qb][s]));
         }
     }
     // union of the wave's rows' ranges per space: a masked tile outside it is skipped by the whole wave
@@ -593,7 +703,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
     const float sl = a.scale_log2e;
 
+#ifdef KSA_TRACE
+    tr.acc[14] = KSA_NOW() - TK0;
+#endif
     for (int seg = 0; seg < n_seg; ++seg) {
+#ifdef KSA_TRACE
+        const unsigned long long TS0 = KSA_NOW();
+#endif
         const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
         const bool masked = item.seg[seg].masked != 0;
         const int n_tiles = (seg_end - seg_begin + BN - 1) / BN;
@@ -604,10 +720,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         LaneOffsets<D> off;
         if (invariant) lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
 
-        if (!masked && invariant && n_tiles >= 2) {
-#ifdef KSA_DEBUG_SKIP_HOT
-            continue;
-#endif
+        if (!masked && invariant && n_tiles >= 2 && seg_begin % 16 == 0) {
             // ================= pipelined loop over a run of FULL tiles ==================================
             // The loop advances in sub-tiles of 32 keys (2t and 2t+1 for the halves of LDS tile t); see subtile().
             // The accumulators are only touched by VALU in the rare "raise the reference" block between sub-tiles.
@@ -615,43 +728,49 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             auto tile_base = [&](int t) { return (int64_t)aug_row(a, space, seg_begin + t * BN) * a.ks[1]; };
             constexpr int HALF = 32 * (D * 2);   // byte offset of the second 32-key block of a tile
             __syncthreads();                     // earlier readers of the LDS buffers are done
+            // V comes from the key-major copy: rows of one (batch, KV head, index space), keys contiguous
+            const int vt_stride = space == KSA_SPACE_TEXT ? a.nt_pad : a.ns_pad;
+            const __bf16 *vtbase = a.vt + (space == KSA_SPACE_TEXT ? 0 : a.vt_sum_off) +
+                                   ((int64_t)(b * a.n_kv_heads + hkv) * D) * vt_stride + seg_begin;
+            lane_offsets_vt<D>(vt_stride, wave, lane, off);
+            auto issue_vt_tile = [&](int t, int buf_off) {
+#pragma unroll
+                for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(vtbase + t * BN, off.vt[i], lds, buf_off, wave, i);
+            };
             issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
-            issue_tile_load<D>(vbase + tile_base(0), off.v, lds, V0, wave);
+            issue_vt_tile(0, V0);
             issue_tile_load<D>(kbase + tile_base(1), off.k, lds, K0 + T::BYTES, wave);
-            issue_tile_load<D>(vbase + tile_base(1), off.v, lds, V0 + T::BYTES, wave);
+            issue_vt_tile(1, V0 + T::BYTES);
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
-            float sv_a[QB][16], sv_b[QB][16];
+            f32x16 sv_a[QB], sv_b[QB];
             float tmax[QB];
             bool raise = false;
-            {
-                f32x16 s0[QB];
-                qk_only<D>(lds, K0, ll, qreg, s0);
-                // MFMA results must have landed before they are read.  The wait names the accumulators as operands:
-                // that is what orders it behind the MFMAs and in front of the reads.
+            qk_only<D>(lds, K0, ll, qreg, sv_a);
+            // MFMA results must have landed before they are read.  The wait names the registers as operands: that is
+            // what orders it behind the MFMAs and in front of the reads.
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) asm volatile("s_nop 15\n\ts_nop 15" : "+a"(s0[qb]));
+            for (int qb = 0; qb < QB; ++qb) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(sv_a[qb]));
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    float mx = -INFINITY;
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = -INFINITY;
 #pragma unroll
-                    for (int g = 0; g < 16; g += 2) {
-                        sv_a[qb][g] = read_acc(s0[qb], g);
-                        sv_a[qb][g + 1] = read_acc(s0[qb], g + 1);
-                        mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
-                    }
-                    tmax[qb] = max3(mx, mx, other_half(mx));
-                    raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
-                }
-                raise = __builtin_amdgcn_ballot_w64(raise) != 0;
+                for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
+                tmax[qb] = max3(mx, mx, other_half(mx));
+                raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
             }
-            bf16x8 ka_pre[2];
-            ka_pre[0] = read_k_operand<D>(lds, ll.k + K0 + HALF, 0);
-            ka_pre[1] = read_k_operand<D>(lds, ll.k + K0 + HALF, 1);
+            raise = __builtin_amdgcn_ballot_w64(raise) != 0;
+            bf16x8 ka_pre[T::KS];
+#pragma unroll
+            for (int s = 0; s < T::KS; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
             int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
             TileSync<D> sync;
             sync.off = &off;
             sync.wave = wave;
+#ifdef KSA_TRACE
+            const unsigned long long TL0 = KSA_NOW();
+            tr.acc[12] += TL0 - TS0;
+#endif
             for (int t = 0; t < n_tiles; ++t) {
                 // The tile loads bypass the compiler's bookkeeping but share the hardware counter with everything it
                 // loads itself (register reloads from scratch around this loop).  An explicit vmcnt(0) here, where
@@ -661,22 +780,25 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 // the tile after next; past the end of the run the last tile is requested again (into a free buffer)
                 const int64_t tb = tile_base(t + 2 < n_tiles ? t + 2 : n_tiles - 1);
                 sync.kg = kbase + tb;
-                sync.vg = vbase + tb;
+                sync.vg = vtbase + (t + 2 < n_tiles ? t + 2 : n_tiles - 1) * BN;
                 sync.k_dst = K0 + b_ld;
                 sync.v_dst = V0 + b_ld;
                 // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
                 if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, true>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, K0 + b_nxt, oacc, st,
-                                         sl, tmax, sync);
+                raise = subtile<D, true>(lds, ll, qreg, sv_b, sv_a, ka_pre, V0 + b_cur, 0, K0 + b_nxt, oacc, st, sl, tmax, sync KSA_TRACE_PASS);
                 // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
                 // (for the last tile those scores come from a buffer that holds no new tile and are never used)
                 if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, false>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur + HALF, K0 + b_nxt + HALF,
-                                          oacc, st, sl, tmax, sync) &&
+                raise = subtile<D, false>(lds, ll, qreg, sv_a, sv_b, ka_pre, V0 + b_cur, 1, K0 + b_nxt + HALF, oacc, st, sl, tmax,
+                                          sync KSA_TRACE_PASS) &&
                         (t + 1 < n_tiles);
                 const int b_old = b_cur;
                 b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
             }
+#ifdef KSA_TRACE
+            tr.acc[7] += KSA_NOW() - TL0;
+            tr.acc[6] += n_tiles;
+#endif
             continue;
         }
 
@@ -718,8 +840,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             exp_and_pack(sacc, pb, st, sl);
             pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
+#ifdef KSA_TRACE
+        tr.acc[11] += KSA_NOW() - TS0;
+        tr.acc[15] += n_tiles;
+#endif
     }
 
+#ifdef KSA_TRACE
+    const unsigned long long TE0 = KSA_NOW();
+#endif
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -739,6 +868,55 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         if (a.lse && h == 0)
             a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
     }
+#ifdef KSA_TRACE
+    tr.acc[9] = KSA_NOW() - TK0;
+    tr.acc[13] = KSA_NOW() - TE0;
+    tr.acc[8] = wall_clock64() - TW0;
+    tr.acc[10] = 1;
+    if (lane == 0)
+        for (int i = 0; i < 16; ++i) atomicAdd(&ksa_trace_buf[i], tr.acc[i]);
+#endif
+}
+
+// Key-major copy of V for the pipelined loop.  The P V MFMA wants, per lane, eight keys of one head-dim column; V is
+// stored the other way round (a key's head-dim values are contiguous), and the transposing LDS read that bridges the
+// two runs at half the rate of a plain 16-byte read.  This pass therefore writes, per (batch, KV head, index space),
+//   vt[d][64 * t + 8 * pc + e] = V[key 64 * t + 32 * sb + 16 * hf + 8 * (e / 4) + 4 * h + e % 4][d],
+//   pc = 4 * sb + 2 * hf + h,
+// i.e. rows of keys in the compact index space, each run of eight keys ordered the way the score MFMA leaves the
+// weights in a lane's registers (lane half h of the 16-key group hf of the 32-key block sb), so that one 16-byte
+// piece is exactly one lane's operand.  One workgroup transposes one 64-key tile through LDS; keys past the end of
+// the space are written as zeros.
+template <int D>
+__global__ __launch_bounds__(256) void ksa_vt_kernel(const PrefillArgs a, int tiles_text) {
+    constexpr int CH = D / 8;
+    __shared__ __attribute__((aligned(16))) unsigned short raw[64][D + 8];
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const int b = blockIdx.z, hkv = blockIdx.y, tid = threadIdx.x;
+    int t = blockIdx.x, space = KSA_SPACE_TEXT;
+    if (t >= tiles_text) t -= tiles_text, space = KSA_SPACE_SUMMARY;
+    const int n_space = space == KSA_SPACE_TEXT ? a.n_text : a.n_sum;
+    const int stride = space == KSA_SPACE_TEXT ? a.nt_pad : a.ns_pad;
+    const int k0 = t * 64;
+    const __bf16 *vb = a.v + b * a.ks[0] + hkv * a.ks[2];
+    for (int idx = tid; idx < 64 * CH; idx += 256) {
+        const int row = idx / CH, ch = idx % CH;
+        u16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k0 + row < n_space)
+            x = *reinterpret_cast<const u16x8 *>(vb + (int64_t)aug_row(a, space, k0 + row) * a.ks[1] + ch * 8);
+        *reinterpret_cast<u16x8 *>(&raw[row][ch * 8]) = x;
+    }
+    __syncthreads();
+    __bf16 *out = const_cast<__bf16 *>(a.vt) + (space == KSA_SPACE_TEXT ? 0 : a.vt_sum_off) +
+                  ((int64_t)(b * a.n_kv_heads + hkv) * D) * stride + k0;
+    for (int idx = tid; idx < D * 8; idx += 256) {
+        const int d = idx >> 3, pc = idx & 7;
+        const int first = 32 * (pc >> 2) + 16 * ((pc >> 1) & 1) + 4 * (pc & 1);
+        u16x8 x;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = raw[first + 8 * (e / 4) + e % 4][d];
+        *reinterpret_cast<u16x8 *>(out + (int64_t)d * stride + 8 * pc) = x;
+    }
 }
 
 int log2_exact(int x) {
@@ -749,6 +927,23 @@ int log2_exact(int x) {
 }
 
 }  // namespace
+
+size_t ksa_prefill_workspace_size(const ksa_params &p) {
+    const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
+    const int64_t keys = (p.n_text + 63) / 64 * 64 + (n_sum + 63) / 64 * 64;
+    return (size_t)((int64_t)p.batch * p.n_kv_heads * p.head_dim * keys * 2);
+}
+
+#ifdef KSA_TRACE
+extern "C" int ksa_debug_trace(unsigned long long *out16, int reset) {
+    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(ksa_trace_buf), 16 * sizeof(unsigned long long)) != hipSuccess) return -1;
+    if (reset) {
+        unsigned long long z[16] = {0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(ksa_trace_buf), z, sizeof(z)) != hipSuccess) return -1;
+    }
+    return 0;
+}
+#endif
 
 int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     PrefillArgs a;
@@ -772,6 +967,14 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     a.aug_len = L.aug_len;
     a.scale = L.p.softmax_scale;
     a.scale_log2e = L.p.softmax_scale * 1.4426950408889634f;
+    a.n_kv_heads = L.p.n_kv_heads;
+    a.n_text = L.p.n_text;
+    a.n_sum = (L.p.n_text / L.p.chunk_len) * L.p.n_summary;
+    a.nt_pad = (a.n_text + 63) / 64 * 64;
+    a.ns_pad = (a.n_sum + 63) / 64 * 64;
+    a.vt = static_cast<const __bf16 *>(L.workspace);
+    a.vt_sum_off = (int64_t)L.p.batch * L.p.n_kv_heads * L.p.head_dim * a.nt_pad;
+    if (!L.workspace || L.workspace_bytes < ksa_prefill_workspace_size(L.p)) return KSA_ERR_WORKSPACE_TOO_SMALL;
     if (L.n_entries <= 0) return KSA_OK;
     // lane offsets inside one tile are 32-bit element offsets: a tile of 64 rows of one index space spans at
     // most (64 / period + 2) chunks of the augmented sequence
@@ -780,6 +983,17 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
         if (L.kv_strides[1] * ((BN / period + 2) * (int64_t)a.w) >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        const int tiles_text = a.nt_pad / 64, tiles_sum = a.ns_pad / 64;
+        const dim3 grid(tiles_text + tiles_sum, L.p.n_kv_heads, L.p.batch);
+        if (L.p.head_dim == 128)
+            hipLaunchKernelGGL(ksa_vt_kernel<128>, grid, dim3(256), 0, st, a, tiles_text);
+        else if (L.p.head_dim == 64)
+            hipLaunchKernelGGL(ksa_vt_kernel<64>, grid, dim3(256), 0, st, a, tiles_text);
+        else
+            return KSA_ERR_UNSUPPORTED;
+        if (hipGetLastError() != hipSuccess) return KSA_ERR_HIP;
+    }
     if (L.p.head_dim == 128)
         hipLaunchKernelGGL(ksa_prefill_kernel<128>, dim3(L.n_entries), dim3(NW * 64), 0, st, a);
     else if (L.p.head_dim == 64)

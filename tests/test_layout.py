@@ -190,8 +190,14 @@ def test_bad_arguments_are_reported_without_a_gpu():
     with pytest.raises(K.KsaError):
         K.ksa_decode_ranges(p, 128)
     # null tensors are rejected before any HIP call
-    rc = binding.lib().ksa_prefill_fwd(lay.handle, None, None, None, None, None, None, None, None, None)
+    rc = binding.lib().ksa_prefill_fwd(lay.handle, None, None, None, None, None, None, None, None, None, 0, None)
     assert rc == -1
+    # a workspace that is too small is reported as such (fake, never dereferenced, 16-byte aligned addresses)
+    fake = ctypes.c_void_p(4096)
+    need = K.prefill_workspace_bytes(lay)
+    assert need == 1 * 2 * 64 * (128 + 64) * 2          # batch * Hkv * d * (n_text + 16 summaries rounded up to 64) bf16
+    rc = binding.lib().ksa_prefill_fwd(lay.handle, fake, fake, fake, fake, None, None, None, None, fake, need - 1, None)
+    assert rc == -3
     rc = binding.lib().ksa_decode_fwd(ctypes.byref(p), None, None, None, None, None, None, None, None, 0, 0, None)
     assert rc == -1
     assert binding.status_string(-3) == "workspace too small"
