@@ -88,6 +88,8 @@ int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v
     a.items = static_cast<const KsaWorkItem *>(lay->d_items);
     a.entries = static_cast<const KsaWgEntry *>(lay->d_entries);
     a.n_entries = (int32_t)lay->entries.size();
+    a.n_pipelined_items = lay->n_pipelined_items;
+    a.n_generic_items = (int32_t)lay->items.size() - lay->n_pipelined_items;
     a.p = p;
     a.aug_len = lay->aug_len;
     a.workspace = workspace;

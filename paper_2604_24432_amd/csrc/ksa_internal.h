@@ -13,6 +13,7 @@ struct ksa_layout {
     int32_t n_chunks;     // J
     std::vector<KsaWorkItem> items;   // one per query tile, heaviest first
     std::vector<KsaWgEntry> entries;  // one per workgroup of the prefill launch
+    int32_t n_pipelined_items = 0;    // items with KsaWorkItem::pipelined set
     // device copies (owned), valid on `device` once uploaded
     int device = -1;
     void *d_items = nullptr;
@@ -31,6 +32,7 @@ struct KsaPrefillLaunch {
     const KsaWorkItem *items;
     const KsaWgEntry *entries;
     int32_t n_entries;
+    int32_t n_pipelined_items, n_generic_items;   // how many work items each of the two kernels owns
     ksa_params p;
     int64_t aug_len;
     void *workspace;          // key-major copy of V, written by the launch itself

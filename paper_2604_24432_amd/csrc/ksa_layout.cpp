@@ -88,6 +88,24 @@ KsaWorkItem summary_item(const ksa_params &p, int64_t u0, int32_t cnt) {
     return it;
 }
 
+// Can the kernel walk every key run of the item with its pipelined loop?  That loop computes each lane's row
+// offsets once per run and reads V from a key-major copy whose keys are permuted in groups of 16, so it needs
+//   - tiles that all start at the same phase of the chunk pattern (64 % period == 0) or never cross a chunk
+//     (period % 64 == 0 and an aligned start), period = c for text keys and m for summary keys,
+//   - a run that starts at a multiple of 16, and
+//   - a last tile that ends inside the index space (all 64 rows of every tile exist).
+bool item_pipelined(const ksa_params &p, const KsaWorkItem &it) {
+    const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
+    for (int s = 0; s < it.n_seg; ++s) {
+        const KsaSegment &g = it.seg[s];
+        const int64_t period = g.space == KSA_SPACE_TEXT ? p.chunk_len : p.n_summary;
+        const int64_t n_space = g.space == KSA_SPACE_TEXT ? p.n_text : n_sum;
+        const bool invariant = (KSA_K_TILE % period == 0) || (period % KSA_K_TILE == 0 && g.begin % KSA_K_TILE == 0);
+        if (!invariant || g.begin % 16 != 0 || g.begin + (int64_t)tiles_in(g) * KSA_K_TILE > n_space) return false;
+    }
+    return true;
+}
+
 // Launch order.  Workgroups are dealt to the 8 XCDs round-robin by workgroup id, and each XCD has its
 // own L2: queue q (workgroup ids congruent to q mod 8) is given whole (batch, KV head) groups so that the
 // workgroups running together on one XCD stream the same K/V rows, and items go heaviest first so the
@@ -167,6 +185,10 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
     const int64_t n_sum = (int64_t)lay->n_chunks * p.n_summary;
     for (int64_t u0 = 0; u0 < n_sum; u0 += KSA_Q_TILE)
         lay->items.push_back(summary_item(p, u0, (int32_t)std::min<int64_t>(KSA_Q_TILE, n_sum - u0)));
+    for (KsaWorkItem &it : lay->items) {
+        it.pipelined = item_pipelined(p, it) ? 1 : 0;
+        lay->n_pipelined_items += it.pipelined;
+    }
     std::stable_sort(lay->items.begin(), lay->items.end(),
                      [](const KsaWorkItem &a, const KsaWorkItem &b) { return a.n_tiles > b.n_tiles; });
     build_entries(*lay);

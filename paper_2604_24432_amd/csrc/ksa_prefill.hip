@@ -29,6 +29,8 @@
 // integer compares per score.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ksa_internal.h"
 
 namespace {
@@ -54,7 +56,10 @@ constexpr int BN = KSA_K_TILE;                // keys per tile
 constexpr int QB = KSA_Q_TILE / (NW * 32);    // 32-row query blocks per wave
 static_assert(KSA_Q_TILE == NW * QB * 32, "query tile must be a whole number of 32-row blocks per wave");
 static_assert(BN == 64, "key tile is two 32-key MFMA blocks");
-constexpr float RESCALE_THRESHOLD_LOG2 = 8.0f;   // raise the running max only for a jump above 2^8
+#ifndef KSA_THR
+#define KSA_THR 8.0f
+#endif
+constexpr float RESCALE_THRESHOLD_LOG2 = KSA_THR;   // raise the running max only for a jump above 2^8
 
 #ifdef KSA_TRACE
 // development only: cycle counts of the pieces of the pipelined loop, summed over every wave
@@ -282,15 +287,12 @@ __device__ __forceinline__ bool tile_max(const f32x16 (&sacc)[QB][2], const RowS
     return __builtin_amdgcn_ballot_w64(raise) != 0;   // wave-uniform
 }
 
-// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators.
-// The accumulators live in accumulation registers (where the MFMAs want them).  The scaling is written as inline
-// assembly with AGPR operands: left to the compiler, the copies to ordinary VGPRs that a plain multiply needs are
-// hoisted out of this rarely taken block into the loop around it, where they drain the MFMA pipe on every tile.
+// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators (which the
+// build keeps in VGPRs, so a plain multiply is all it takes).  Rarely taken: see RESCALE_THRESHOLD_LOG2.
 template <int D>
 __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
                                                 float sl) {
     using T = Tile<D>;
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // let the last MFMA results reach the register file
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float m_new = fmaxf(st.m_ref[qb], tmax[qb]);
@@ -301,15 +303,8 @@ __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                float acc = oacc[qb][db][g], tmp;
-                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
-                             : "+a"(acc), "=&v"(tmp)
-                             : "v"(alpha));
-                oacc[qb][db][g] = acc;
-            }
+            for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
     }
-    asm volatile("s_nop 7" ::: "memory");
     // Register spills around this block are reloaded from scratch memory.  Waiting for them here keeps the compiler
     // from placing its own s_waitcnt vmcnt(0) after the block rejoins the loop, where it would also wait for the
     // LDS-direct tile loads in flight (the hardware counter is shared) on every tile.
@@ -369,19 +364,20 @@ __device__ __forceinline__ bf16x8 read_vt_operand(const unsigned char *lds, int 
     return *reinterpret_cast<const bf16x8 *>(lds + ((lvt ^ (hf << 5)) + db * 4096));
 }
 
-// Score MFMA with its result in ordinary VGPRs.  The scores are consumed by VALU code (exp2, max); the compiler
-// places MFMA results in accumulation registers, and every v_accvgpr_read of one of them while other MFMAs are in
-// flight was measured to cost about as much as an exponential.  Written as inline assembly, the instruction's
-// register classes are ours to choose: result VGPRs, K operand VGPRs (fresh from LDS), Q operand accumulation
-// registers (resident for the whole kernel, never touched by VALU).
-// The compiler does not know that these statements are MFMAs, so it inserts none of the wait states an MFMA result
-// needs before VALU code may read it: callers keep every read at least two later MFMAs away.
+// The scores are consumed by VALU code (exp2, max), so the score MFMAs should leave them in ordinary VGPRs: with the
+// results in accumulation registers every score costs a v_accvgpr_read, and such a read while other MFMAs are in
+// flight was measured to cost about as much as an exponential.  The library is built with the compiler option that
+// gives MFMA results and accumulator inputs VGPRs (-mllvm -amdgpu-mfma-vgpr-form), which covers this kernel's output
+// accumulators as well; register allocation, copies and the wait states an MFMA result needs before VALU code may
+// read it all stay with the compiler.
 __device__ __forceinline__ void score_mfma_first(f32x16 &acc, const bf16x8 &k_op, const bf16x8 &q_op) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_op), "a"(q_op));
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op, q_op, f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0);
 }
 __device__ __forceinline__ void score_mfma_next(f32x16 &acc, const bf16x8 &k_op, const bf16x8 &q_op) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_op), "a"(q_op));
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_op, q_op, acc, 0, 0, 0);
 }
+// Reads of the tuple written after this statement stay behind it, i.e. in the slot they were written for.
+__device__ __forceinline__ void scores_ready(f32x16 &acc) { asm volatile("" : "+v"(acc)); }
 
 // Scores of one 32-key block alone (pipeline fill).
 template <int D>
@@ -448,11 +444,12 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // and the V operands during the score slots: every LDS read is issued a whole phase before its first use.  With SYNC
 // the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true if
 // some row of the next scores exceeds its reference maximum by more than the threshold.
-template <int D, bool SYNC>
+template <int D, bool SYNC, bool MASKED>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
                                         f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::KS],
                                         int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st, float sl,
-                                        float (&tmax)[QB], const TileSync<D> &sync KSA_TRACE_ARG) {
+                                        float (&tmax)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
+                                        const int (&vis_span)[QB] KSA_TRACE_ARG) {
     using T = Tile<D>;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of the P V phase
@@ -479,6 +476,9 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         rsum[qb] = st.l_part[qb];
         mx[qb] = -INFINITY;
     }
+    int mask_base[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) mask_base[qb] = MASKED ? next_key0 - vis_lo[qb] : 0;
     bf16x8 p[QB][2];
     bf16x8 va[NSTEP];
     float xs[NE], ws[NE];
@@ -525,6 +525,15 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         for (int j = 0; j < NR; ++j)
             if (slot_of_r(j) == u) {
                 const int qb = j / 8, g = 2 * (j % 8);
+                if (MASKED) {
+                    // key of score register g: next_key0 + 4 * (lane / 32) + 8 * (g / 4) + g % 4; visible iff it lies in
+                    // [lo, lo + span); vis_lo holds lo - 4 * (lane / 32)
+#pragma unroll
+                    for (int x = g; x < g + 2; ++x) {
+                        const unsigned rel = (unsigned)(mask_base[qb] + (8 * (x / 4) + x % 4));
+                        sv_next[qb][x] = rel < (unsigned)vis_span[qb] ? sv_next[qb][x] : -INFINITY;
+                    }
+                }
                 mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
             }
 #endif
@@ -587,6 +596,11 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
 #if !(defined(KSA_ABL) && (KSA_ABL & 2))
         if (qb == QB - 1) ka[x] = read_k_operand<D>(lds, lkn, x);   // K operands of the following sub-tile
 #endif
+        if (N1 + u == R_FIRST) {
+            // from here on the next scores may be read
+#pragma unroll
+            for (int q2 = 0; q2 < QB; ++q2) scores_ready(sv_next[q2]);
+        }
         valu_slice(N1 + u);
         if (u == N2 - 1) {
 #pragma unroll
@@ -605,7 +619,10 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
     return __builtin_amdgcn_ballot_w64(raise) != 0;
 }
 
-template <int D>
+// PIPELINED = true: work items all of whose key runs satisfy the conditions of the pipelined loop (the scheduler
+// marks them); false: the remaining items, walked with the plain loop.  Two instantiations rather than one kernel
+// with both loops keep the register allocation of the pipelined loop free of the plain loop's temporaries.
+template <int D, bool PIPELINED>
 __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs a) {
     using T = Tile<D>;
     // three K tiles, then three V tiles: the pipelined loop loads two tiles ahead with one barrier per tile
@@ -621,6 +638,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
+    if ((item.pipelined != 0) != PIPELINED) return;
     const int b = ent.batch, hq = ent.q_head, hkv = hq / a.group;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -666,9 +684,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16);
             else
                 qreg[qb][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            // From here on the Q operand is a value of the accumulation-register class: the score MFMAs name it as
-            // such, and without this the compiler re-copies it in front of every one of them.
-            asm volatile("" : "+a"(qreg[qb][s]));
         }
     }
     // union of the wave's rows' ranges per space: a masked tile outside it is skipped by the whole wave
@@ -720,14 +735,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         LaneOffsets<D> off;
         if (invariant) lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
 
-        if (!masked && invariant && n_tiles >= 2 && seg_begin % 16 == 0) {
-            // ================= pipelined loop over a run of FULL tiles ==================================
+        if constexpr (PIPELINED) {
+            // (the scheduler guarantees: lane offsets invariant over the run, seg_begin % 16 == 0, and the run's last
+            // tile ends inside its index space, so every row of every tile exists)
+            // ================= pipelined loop over a run of tiles =======================================
             // The loop advances in sub-tiles of 32 keys (2t and 2t+1 for the halves of LDS tile t); see subtile().
             // The accumulators are only touched by VALU in the rare "raise the reference" block between sub-tiles.
             // LDS tile t lives in buffer t % 3; tile t+2 is requested right after the one barrier of tile t.
+            // A MASKED run differs in one place: every score is clipped to its row's visible key range when it is
+            // looked at for the row maximum.  (Every row of every tile exists: the run ends inside its index space.)
             auto tile_base = [&](int t) { return (int64_t)aug_row(a, space, seg_begin + t * BN) * a.ks[1]; };
             constexpr int HALF = 32 * (D * 2);   // byte offset of the second 32-key block of a tile
-            __syncthreads();                     // earlier readers of the LDS buffers are done
             // V comes from the key-major copy: rows of one (batch, KV head, index space), keys contiguous
             const int vt_stride = space == KSA_SPACE_TEXT ? a.nt_pad : a.ns_pad;
             const __bf16 *vtbase = a.vt + (space == KSA_SPACE_TEXT ? 0 : a.vt_sum_off) +
@@ -737,71 +755,114 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
 #pragma unroll
                 for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(vtbase + t * BN, off.vt[i], lds, buf_off, wave, i);
             };
-            issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
-            issue_vt_tile(0, V0);
-            issue_tile_load<D>(kbase + tile_base(1), off.k, lds, K0 + T::BYTES, wave);
-            issue_vt_tile(1, V0 + T::BYTES);
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            f32x16 sv_a[QB], sv_b[QB];
-            float tmax[QB];
-            bool raise = false;
-            qk_only<D>(lds, K0, ll, qreg, sv_a);
-            // MFMA results must have landed before they are read.  The wait names the registers as operands: that is
-            // what orders it behind the MFMAs and in front of the reads.
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(sv_a[qb]));
+            // visible key range of each of the lane's rows inside this run: [lo, lo + span), lo stored minus 4 * h
+            int vis_lo[QB], vis_span[QB];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
-                tmax[qb] = max3(mx, mx, other_half(mx));
-                raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+                const int lo = max(space == KSA_SPACE_TEXT ? lo_t[qb] : lo_s[qb], seg_begin);
+                const int hi = min(space == KSA_SPACE_TEXT ? hi_t[qb] : hi_s[qb], seg_end);
+                vis_lo[qb] = lo - 4 * h;
+                vis_span[qb] = max(hi - lo, 0);
             }
-            raise = __builtin_amdgcn_ballot_w64(raise) != 0;
-            bf16x8 ka_pre[T::KS];
+            auto run = [&](auto masked_tag) {
+                constexpr bool MASKED = decltype(masked_tag)::value;
+                const int second = n_tiles > 1 ? 1 : 0;
+                __syncthreads();                     // earlier readers of the LDS buffers are done
+                issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
+                issue_vt_tile(0, V0);
+                issue_tile_load<D>(kbase + tile_base(second), off.k, lds, K0 + T::BYTES, wave);
+                issue_vt_tile(second, V0 + T::BYTES);
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+                f32x16 sv_a[QB], sv_b[QB];
+                float tmax[QB];
+                bool raise = false;
+                qk_only<D>(lds, K0, ll, qreg, sv_a);
 #pragma unroll
-            for (int s = 0; s < T::KS; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
-            int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
-            TileSync<D> sync;
-            sync.off = &off;
-            sync.wave = wave;
+                for (int qb = 0; qb < QB; ++qb) scores_ready(sv_a[qb]);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    if (MASKED) {
+#pragma unroll
+                        for (int g = 0; g < 16; ++g) {
+                            const unsigned rel = (unsigned)(seg_begin - vis_lo[qb] + (8 * (g / 4) + g % 4));
+                            sv_a[qb][g] = rel < (unsigned)vis_span[qb] ? sv_a[qb][g] : -INFINITY;
+                        }
+                    }
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
+                    tmax[qb] = max3(mx, mx, other_half(mx));
+                    raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+                }
+                raise = __builtin_amdgcn_ballot_w64(raise) != 0;
+                bf16x8 ka_pre[T::KS];
+#pragma unroll
+                for (int s = 0; s < T::KS; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
+                int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
+                TileSync<D> sync;
+                sync.off = &off;
+                sync.wave = wave;
 #ifdef KSA_TRACE
-            const unsigned long long TL0 = KSA_NOW();
-            tr.acc[12] += TL0 - TS0;
+                const unsigned long long TL0 = KSA_NOW();
+                tr.acc[12] += TL0 - TS0;
 #endif
-            for (int t = 0; t < n_tiles; ++t) {
-                // The tile loads bypass the compiler's bookkeeping but share the hardware counter with everything it
-                // loads itself (register reloads from scratch around this loop).  An explicit vmcnt(0) here, where
-                // only the loads of tile t+1 are in flight and are about to be needed anyway, keeps it from placing
-                // its own wait further down, behind the requests for tile t+2.
+                for (int t = 0; t < n_tiles; ++t) {
+                    // The tile loads bypass the compiler's bookkeeping but share the hardware counter with everything
+                    // it loads itself (register reloads from scratch around this loop).  An explicit vmcnt(0) here,
+                    // where only the loads of tile t+1 are in flight and are about to be needed anyway, keeps it from
+                    // placing its own wait further down, behind the requests for tile t+2.
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    // the tile after next; past the end of the run the last tile is requested again (into a free buffer)
+                    const int t_ld = t + 2 < n_tiles ? t + 2 : n_tiles - 1;
+                    sync.kg = kbase + tile_base(t_ld);
+                    sync.vg = vtbase + t_ld * BN;
+                    sync.k_dst = K0 + b_ld;
+                    sync.v_dst = V0 + b_ld;
+                    const int key0 = seg_begin + t * BN;
+#if defined(KSA_DBG_SYNC) && (KSA_DBG_SYNC & 1)
+                    __syncthreads();
+#endif
+                    // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
+#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 1)
+                    raise = true;
+#endif
+#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
+                    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+                    if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                    raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, V0 + b_cur, 0, K0 + b_nxt, oacc, st, sl, tmax,
+                                                     sync, key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
+#if defined(KSA_DBG_SYNC) && (KSA_DBG_SYNC & 2)
+                    __syncthreads();
+#endif
+                    // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
+                    // (for the last tile those scores come from a buffer that holds no new tile and are never used)
+#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 2)
+                    raise = true;
+#endif
+#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
+                    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+                    if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                    raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, V0 + b_cur, 1, K0 + b_nxt + HALF, oacc, st, sl,
+                                                      tmax, sync, key0 + BN, vis_lo, vis_span KSA_TRACE_PASS) &&
+                            (t + 1 < n_tiles);
+                    const int b_old = b_cur;
+                    b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
+                }
+                // the request repeated for the last tile is still in flight: let it land before anyone reuses LDS
                 __builtin_amdgcn_s_waitcnt(0x0F70);
-                // the tile after next; past the end of the run the last tile is requested again (into a free buffer)
-                const int64_t tb = tile_base(t + 2 < n_tiles ? t + 2 : n_tiles - 1);
-                sync.kg = kbase + tb;
-                sync.vg = vtbase + (t + 2 < n_tiles ? t + 2 : n_tiles - 1) * BN;
-                sync.k_dst = K0 + b_ld;
-                sync.v_dst = V0 + b_ld;
-                // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
-                if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, true>(lds, ll, qreg, sv_b, sv_a, ka_pre, V0 + b_cur, 0, K0 + b_nxt, oacc, st, sl, tmax, sync KSA_TRACE_PASS);
-                // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
-                // (for the last tile those scores come from a buffer that holds no new tile and are never used)
-                if (raise) raise_reference<D>(st, tmax, oacc, sl);
-                raise = subtile<D, false>(lds, ll, qreg, sv_a, sv_b, ka_pre, V0 + b_cur, 1, K0 + b_nxt + HALF, oacc, st, sl, tmax,
-                                          sync KSA_TRACE_PASS) &&
-                        (t + 1 < n_tiles);
-                const int b_old = b_cur;
-                b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
-            }
 #ifdef KSA_TRACE
-            tr.acc[7] += KSA_NOW() - TL0;
-            tr.acc[6] += n_tiles;
+                tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TL0;
+                tr.acc[MASKED ? 15 : 6] += n_tiles;
 #endif
-            continue;
-        }
-
+            };
+            if (masked)
+                run(std::true_type{});
+            else
+                run(std::false_type{});
+        } else {
         // ================= plain loop: MASKED runs, short runs, odd chunk shapes ============================
         const int wlo = space == KSA_SPACE_TEXT ? wlo_t : wlo_s, whi = space == KSA_SPACE_TEXT ? whi_t : whi_s;
         for (int kt = seg_begin; kt < seg_end; kt += BN) {
@@ -840,9 +901,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             exp_and_pack(sacc, pb, st, sl);
             pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
+        }
 #ifdef KSA_TRACE
-        tr.acc[11] += KSA_NOW() - TS0;
-        tr.acc[15] += n_tiles;
+        if (!PIPELINED) {
+            tr.acc[11] += KSA_NOW() - TS0;
+            tr.acc[15] += n_tiles;
+        }
 #endif
     }
 
@@ -994,11 +1058,15 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
             return KSA_ERR_UNSUPPORTED;
         if (hipGetLastError() != hipSuccess) return KSA_ERR_HIP;
     }
-    if (L.p.head_dim == 128)
-        hipLaunchKernelGGL(ksa_prefill_kernel<128>, dim3(L.n_entries), dim3(NW * 64), 0, st, a);
-    else if (L.p.head_dim == 64)
-        hipLaunchKernelGGL(ksa_prefill_kernel<64>, dim3(L.n_entries), dim3(NW * 64), 0, st, a);
-    else
+    const dim3 grid(L.n_entries), block(NW * 64);
+    if (L.p.head_dim == 128) {
+        if (L.n_pipelined_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, true>), grid, block, 0, st, a);
+        if (L.n_generic_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, false>), grid, block, 0, st, a);
+    } else if (L.p.head_dim == 64) {
+        if (L.n_pipelined_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, true>), grid, block, 0, st, a);
+        if (L.n_generic_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, false>), grid, block, 0, st, a);
+    } else {
         return KSA_ERR_UNSUPPORTED;
+    }
     return hipGetLastError() == hipSuccess ? KSA_OK : KSA_ERR_HIP;
 }

@@ -31,7 +31,8 @@ struct KsaWorkItem {
     int32_t n_seg;
     KsaSegment seg[KSA_MAX_SEGMENTS];
     int32_t n_tiles;   // key tiles over all segments (the item's cost)
-    int32_t pad[3];
+    int32_t pipelined; // 1: every segment meets the conditions of the kernel's pipelined loop (see ksa_item_pipelined)
+    int32_t pad[2];
 };
 
 // What workgroup blockIdx.x does: item < 0 means nothing.
