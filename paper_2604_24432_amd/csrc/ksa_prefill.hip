@@ -287,12 +287,18 @@ __device__ __forceinline__ bool tile_max(const f32x16 (&sacc)[QB][2], const RowS
     return __builtin_amdgcn_ballot_w64(raise) != 0;   // wave-uniform
 }
 
-// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators (which the
-// build keeps in VGPRs, so a plain multiply is all it takes).  Rarely taken: see RESCALE_THRESHOLD_LOG2.
-template <int D>
+// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators.  Rarely
+// taken: see RESCALE_THRESHOLD_LOG2.
+// IN_AGPRS = false: the accumulators are ordinary values of the compiler (generic kernel): a plain multiply.
+// IN_AGPRS = true (pipelined kernel): the accumulators live in accumulation registers and are only ever touched by
+// the inline-assembly MFMAs of pv_mfma_raw() and by this routine, which scales them in place, also in assembly:
+// left to the compiler, the copies to VGPRs that a plain multiply needs get hoisted out of this block into the loop
+// around it, where they would drain the MFMA pipe on every tile.
+template <int D, bool IN_AGPRS>
 __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
                                                 float sl) {
     using T = Tile<D>;
+    if (IN_AGPRS) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results reach the register file
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float m_new = fmaxf(st.m_ref[qb], tmax[qb]);
@@ -303,12 +309,40 @@ __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
+            for (int g = 0; g < 16; ++g) {
+                if (IN_AGPRS) {
+                    float acc = oacc[qb][db][g], tmp;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(acc), "=&v"(tmp)
+                                 : "v"(alpha));
+                    oacc[qb][db][g] = acc;
+                } else {
+                    oacc[qb][db][g] *= alpha;
+                }
+            }
     }
+    if (IN_AGPRS) asm volatile("s_nop 7" ::: "memory");
     // Register spills around this block are reloaded from scratch memory.  Waiting for them here keeps the compiler
     // from placing its own s_waitcnt vmcnt(0) after the block rejoins the loop, where it would also wait for the
     // LDS-direct tile loads in flight (the hardware counter is shared) on every tile.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+}
+
+// O^T += V^T P^T with the accumulator in accumulation registers, whatever the build's default for MFMA results is.
+// The compiler does not know that this statement is an MFMA: nothing but further pv_mfma_raw() statements and
+// raise_reference<IN_AGPRS>() may touch the accumulators until accumulators_settle() has run.
+__device__ __forceinline__ void pv_mfma_raw(f32x16 &acc, const bf16x8 &v_op, const bf16x8 &p_op) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_op), "v"(p_op));
+}
+// Waits until the last pv_mfma_raw() results are in the register file; later accesses stay behind it.
+template <int D>
+__device__ __forceinline__ void accumulators_settle(f32x16 (&oacc)[QB][Tile<D>::DB]) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[0][0]));
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int db = 0; db < Tile<D>::DB; ++db)
+            if (qb + db > 0) asm volatile("" : "+a"(oacc[qb][db]));
 }
 
 // p = 2^((s - m_ref) * scale * log2 e) rounded to bf16 in the B-operand layout of P V.  The row sum adds up the
@@ -568,7 +602,7 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
     for (int u = 0; u < N2; ++u) {
         const int x = u / QB, qb = u % QB;
         const int hf = x / T::DB, db = x % T::DB;
-        oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[x], p[qb][hf], oacc[qb][db], 0, 0, 0);
+        pv_mfma_raw(oacc[qb][db], va[x], p[qb][hf]);
         if (SYNC) {
             if (u == 0) {
 #ifdef KSA_TRACE
@@ -830,7 +864,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
 #if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
                     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #endif
-                    if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                    if (raise) raise_reference<D, true>(st, tmax, oacc, sl);
                     raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, V0 + b_cur, 0, K0 + b_nxt, oacc, st, sl, tmax,
                                                      sync, key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
 #if defined(KSA_DBG_SYNC) && (KSA_DBG_SYNC & 2)
@@ -844,7 +878,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
 #if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
                     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #endif
-                    if (raise) raise_reference<D>(st, tmax, oacc, sl);
+                    if (raise) raise_reference<D, true>(st, tmax, oacc, sl);
                     raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, V0 + b_cur, 1, K0 + b_nxt + HALF, oacc, st, sl,
                                                       tmax, sync, key0 + BN, vis_lo, vis_span KSA_TRACE_PASS) &&
                             (t + 1 < n_tiles);
@@ -853,6 +887,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 }
                 // the request repeated for the last tile is still in flight: let it land before anyone reuses LDS
                 __builtin_amdgcn_s_waitcnt(0x0F70);
+                accumulators_settle<D>(oacc);
 #ifdef KSA_TRACE
                 tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TL0;
                 tr.acc[MASKED ? 15 : 6] += n_tiles;
@@ -897,7 +932,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             }
             bf16x8 pb[QB][2][2];
             float tmax[QB];
-            if (tile_max(sacc, st, sl, tmax)) raise_reference<D>(st, tmax, oacc, sl);
+            if (tile_max(sacc, st, sl, tmax)) raise_reference<D, false>(st, tmax, oacc, sl);
             exp_and_pack(sacc, pb, st, sl);
             pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
