@@ -141,6 +141,14 @@ int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void
                     const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * ksa_prefill_relayout_v: only the first kernel of ksa_prefill_fwd, the one that writes the key-major copy of
+ * V into the workspace (same v, kv_strides, workspace and error rules as there).  ksa_prefill_fwd always runs it
+ * itself; this entry point exists so that the two kernels can be timed apart.
+ */
+int ksa_prefill_relayout_v(ksa_layout *layout, const void *v, const int64_t kv_strides[3], void *workspace,
+                           size_t workspace_bytes, void *stream);
+
 /* ---- decode over the summary KV cache (section 2.3.1) ------------------------------------------ */
 
 /*

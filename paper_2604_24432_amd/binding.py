@@ -68,6 +68,7 @@ def lib():
         "ksa_layout_launch_order": (C.c_int, [vp, i64p, vp, vp, vp, vp]),
         "ksa_prefill_workspace_bytes": (C.c_size_t, [vp]),
         "ksa_prefill_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64p, i64p, i64p, vp, C.c_size_t, vp]),
+        "ksa_prefill_relayout_v": (C.c_int, [vp, vp, i64p, vp, C.c_size_t, vp]),
         "ksa_cache_geometry": (C.c_int, [pp, i32p, i32p]),
         "ksa_cache_text_row": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_cache_summary_row": (C.c_int, [pp, C.c_int64, i32p]),
@@ -86,7 +87,7 @@ def lib():
 
 EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload", "ksa_layout_dims",
                     "ksa_layout_index_maps", "ksa_layout_row_ranges", "ksa_layout_mask_row",
-                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_cache_geometry", "ksa_cache_text_row",
+                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v", "ksa_cache_geometry", "ksa_cache_text_row",
                     "ksa_cache_summary_row", "ksa_decode_ranges", "ksa_decode_workspace_bytes",
                     "ksa_decode_fwd", "ksa_status_string", "ksa_build_info")
 
@@ -230,6 +231,15 @@ def ksa_prefill_fwd(layout: Layout, q, k, v, o=None, lse=None, return_lse=True, 
                                C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream))
     _check(rc, "ksa_prefill_fwd")
     return o, lse
+
+
+def ksa_prefill_relayout_v(layout: Layout, v, workspace, stream=None):
+    """Only the first kernel of ksa_prefill_fwd (key-major copy of V into the workspace); for timing."""
+    import torch
+    _require(v, "v", torch.bfloat16, 4)
+    rc = lib().ksa_prefill_relayout_v(layout.handle, C.c_void_p(v.data_ptr()), _strides3(v, (0, 1, 2)),
+                                      C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream))
+    _check(rc, "ksa_prefill_relayout_v")
 
 
 def cache_geometry(params: ksa_params) -> Tuple[int, int]:

@@ -68,14 +68,16 @@ int ksa_layout_upload(ksa_layout *lay) {
 
 size_t ksa_prefill_workspace_bytes(const ksa_layout *lay) { return lay ? ksa_prefill_workspace_size(lay->p) : 0; }
 
-int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v, void *o, float *lse,
-                    const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
-                    void *workspace, size_t workspace_bytes, void *stream) {
+namespace {
+
+int prefill_call(ksa_layout *lay, const void *q, const void *k, const void *v, void *o, float *lse,
+                 const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3], void *workspace,
+                 size_t workspace_bytes, void *stream, int32_t phases) {
     if (!lay || !q || !k || !v || !o || !workspace) return KSA_ERR_INVALID_ARG;
-    if (!aligned16(workspace)) return KSA_ERR_INVALID_ARG;
-    if (workspace_bytes < ksa_prefill_workspace_size(lay->p)) return KSA_ERR_WORKSPACE_TOO_SMALL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return KSA_ERR_INVALID_ARG;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return KSA_ERR_INVALID_ARG;
+    if (workspace_bytes < ksa_prefill_workspace_size(lay->p)) return KSA_ERR_WORKSPACE_TOO_SMALL;
     const ksa_params &p = lay->p;
     KsaPrefillLaunch a;
     default_strides(a.q_strides, q_strides, lay->aug_len, p.n_q_heads, p.head_dim);
@@ -94,7 +96,22 @@ int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v
     a.aug_len = lay->aug_len;
     a.workspace = workspace;
     a.workspace_bytes = workspace_bytes;
+    a.phases = phases;
     return ksa_launch_prefill(a, stream);
+}
+
+}  // namespace
+
+int ksa_prefill_fwd(ksa_layout *lay, const void *q, const void *k, const void *v, void *o, float *lse,
+                    const int64_t q_strides[3], const int64_t kv_strides[3], const int64_t o_strides[3],
+                    void *workspace, size_t workspace_bytes, void *stream) {
+    return prefill_call(lay, q, k, v, o, lse, q_strides, kv_strides, o_strides, workspace, workspace_bytes, stream, 3);
+}
+
+int ksa_prefill_relayout_v(ksa_layout *lay, const void *v, const int64_t kv_strides[3], void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    // the attention tensors are not touched in this phase; v stands in for them in the shared argument checks
+    return prefill_call(lay, v, v, v, workspace, nullptr, nullptr, kv_strides, nullptr, workspace, workspace_bytes, stream, 1);
 }
 
 size_t ksa_decode_workspace_bytes(const ksa_params *p, int32_t n_splits) {

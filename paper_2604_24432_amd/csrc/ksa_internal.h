@@ -36,6 +36,7 @@ struct KsaPrefillLaunch {
     ksa_params p;
     int64_t aug_len;
     void *workspace;          // key-major copy of V, written by the launch itself
+    int32_t phases;           // bit 0: write the key-major copy of V; bit 1: run the attention kernels
     size_t workspace_bytes;
 };
 size_t ksa_prefill_workspace_size(const ksa_params &p);

@@ -1082,7 +1082,7 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
         if (L.kv_strides[1] * ((BN / period + 2) * (int64_t)a.w) >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    {
+    if (L.phases & 1) {
         const int tiles_text = a.nt_pad / 64, tiles_sum = a.ns_pad / 64;
         const dim3 grid(tiles_text + tiles_sum, L.p.n_kv_heads, L.p.batch);
         if (L.p.head_dim == 128)
@@ -1093,6 +1093,7 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
             return KSA_ERR_UNSUPPORTED;
         if (hipGetLastError() != hipSuccess) return KSA_ERR_HIP;
     }
+    if (!(L.phases & 2)) return KSA_OK;
     const dim3 grid(L.n_entries), block(NW * 64);
     if (L.p.head_dim == 128) {
         if (L.n_pipelined_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, true>), grid, block, 0, st, a);
