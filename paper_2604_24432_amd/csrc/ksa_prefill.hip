@@ -40,6 +40,9 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
 #define GLOBAL_PTR(T) __attribute__((address_space(1))) T *
@@ -56,10 +59,7 @@ constexpr int BN = KSA_K_TILE;                // keys per tile
 constexpr int QB = KSA_Q_TILE / (NW * 32);    // 32-row query blocks per wave
 static_assert(KSA_Q_TILE == NW * QB * 32, "query tile must be a whole number of 32-row blocks per wave");
 static_assert(BN == 64, "key tile is two 32-key MFMA blocks");
-#ifndef KSA_THR
-#define KSA_THR 8.0f
-#endif
-constexpr float RESCALE_THRESHOLD_LOG2 = KSA_THR;   // raise the running max only for a jump above 2^8
+constexpr float RESCALE_THRESHOLD_LOG2 = 8.0f;   // raise the running max only for a jump above 2^8
 
 #ifdef KSA_TRACE
 // development only: cycle counts of the pieces of the pipelined loop, summed over every wave
@@ -130,6 +130,8 @@ struct Tile {
     static constexpr int KS = D / 16;          // k steps of the score MFMA
     static constexpr int DB = D / 32;          // 32-column blocks of the output
     static constexpr int BYTES = BN * D * 2;
+    // pipelined loop: LDS operand reads are issued this many k steps (two MFMAs each) ahead of their use
+    static constexpr int RING = KS / 4 > 2 ? KS / 4 : 2;
 };
 
 // Per-lane element offsets (relative to the tile's first row) of the 16-byte pieces this lane fetches.
@@ -180,6 +182,15 @@ __device__ __forceinline__ void lane_offsets_vt(int vt_stride, int wave, int lan
 __device__ __forceinline__ void lds_direct_load_16(const __bf16 *src, const unsigned char *dst) {
     const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)dst);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory");
+}
+
+// The same with a wave-uniform base address in scalar registers plus a per-lane unsigned byte offset: nothing but
+// the load itself goes through the vector issue port.
+__device__ __forceinline__ void lds_direct_load_16_s(const __bf16 *sbase, unsigned voff_bytes, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff_bytes), "s"(sbase), "s"(lds_addr)
+                 : "memory");
 }
 
 template <int D>
@@ -268,6 +279,7 @@ __device__ __forceinline__ void pv_mfma(const unsigned char *lds, int buf_off, c
 // the end).
 struct RowState {
     float m_ref[QB], l_part[QB];
+    f32x4 l_quad[QB];   // pipelined kernel: the lane's part of the row sum, kept by sum_quad() (register 0 is read)
 };
 
 // Row maxima of a score tile; returns true if some lane's row exceeds its reference by more than the threshold.
@@ -287,18 +299,12 @@ __device__ __forceinline__ bool tile_max(const f32x16 (&sacc)[QB][2], const RowS
     return __builtin_amdgcn_ballot_w64(raise) != 0;   // wave-uniform
 }
 
-// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators.  Rarely
-// taken: see RESCALE_THRESHOLD_LOG2.
-// IN_AGPRS = false: the accumulators are ordinary values of the compiler (generic kernel): a plain multiply.
-// IN_AGPRS = true (pipelined kernel): the accumulators live in accumulation registers and are only ever touched by
-// the inline-assembly MFMAs of pv_mfma_raw() and by this routine, which scales them in place, also in assembly:
-// left to the compiler, the copies to VGPRs that a plain multiply needs get hoisted out of this block into the loop
-// around it, where they would drain the MFMA pipe on every tile.
-template <int D, bool IN_AGPRS>
+// Raises the reference maxima to the tile maxima and rescales the row sums and the output accumulators (generic
+// kernel).  Rarely taken: see RESCALE_THRESHOLD_LOG2.
+template <int D>
 __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
                                                 float sl) {
     using T = Tile<D>;
-    if (IN_AGPRS) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results reach the register file
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float m_new = fmaxf(st.m_ref[qb], tmax[qb]);
@@ -309,19 +315,45 @@ __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
+            for (int g = 0; g < 16; ++g) oacc[qb][db][g] *= alpha;
+    }
+}
+
+// The pipelined kernel's version.  mx are the LANE's maxima of the pending scores; the two lanes of a row are combined
+// here.  The output accumulators live in accumulation registers and are only ever touched by the inline-assembly
+// MFMAs of pv_mfma_raw() and by this routine, which scales them in place, also in assembly: left to the compiler, the
+// copies to VGPRs that a plain multiply needs get hoisted out of this block into the loop around it, where they would
+// drain the MFMA pipe on every tile.
+template <int D>
+__device__ __forceinline__ void raise_reference_pl(RowState &st, const float (&mx)[QB], f32x16 (&oacc)[QB][Tile<D>::DB],
+                                                   float sl) {
+    using T = Tile<D>;
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results reach the register file
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(st.m_ref[qb], fmaxf(mx[qb], other_half(mx[qb])));
+        // (old - new) first: equal references (also the -1e30 start value) must give exactly 2^0
+        const float alpha = __builtin_amdgcn_exp2f((st.m_ref[qb] - m_new) * sl);
+        st.m_ref[qb] = m_new;
+        {   // the row sum: register 0 is the one that is read
+            float acc = st.l_quad[qb][0], tmp;
+            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                         : "+a"(acc), "=&v"(tmp)
+                         : "v"(alpha));
+            st.l_quad[qb][0] = acc;
+        }
+#pragma unroll
+        for (int db = 0; db < T::DB; ++db)
+#pragma unroll
             for (int g = 0; g < 16; ++g) {
-                if (IN_AGPRS) {
-                    float acc = oacc[qb][db][g], tmp;
-                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
-                                 : "+a"(acc), "=&v"(tmp)
-                                 : "v"(alpha));
-                    oacc[qb][db][g] = acc;
-                } else {
-                    oacc[qb][db][g] *= alpha;
-                }
+                float acc = oacc[qb][db][g], tmp;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(acc), "=&v"(tmp)
+                             : "v"(alpha));
+                oacc[qb][db][g] = acc;
             }
     }
-    if (IN_AGPRS) asm volatile("s_nop 7" ::: "memory");
+    asm volatile("s_nop 7" ::: "memory");
     // Register spills around this block are reloaded from scratch memory.  Waiting for them here keeps the compiler
     // from placing its own s_waitcnt vmcnt(0) after the block rejoins the loop, where it would also wait for the
     // LDS-direct tile loads in flight (the hardware counter is shared) on every tile.
@@ -330,14 +362,16 @@ __device__ __forceinline__ void raise_reference(RowState &st, const float (&tmax
 
 // O^T += V^T P^T with the accumulator in accumulation registers, whatever the build's default for MFMA results is.
 // The compiler does not know that this statement is an MFMA: nothing but further pv_mfma_raw() statements and
-// raise_reference<IN_AGPRS>() may touch the accumulators until accumulators_settle() has run.
-__device__ __forceinline__ void pv_mfma_raw(f32x16 &acc, const bf16x8 &v_op, const bf16x8 &p_op) {
+// raise_reference_pl() may touch the accumulators until accumulators_settle() has run.
+__device__ __forceinline__ void pv_mfma_raw(f32x16 &acc, const bf16x8 &v_op, const u32x4 &p_op) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_op), "v"(p_op));
 }
 // Waits until the last pv_mfma_raw() results are in the register file; later accesses stay behind it.
 template <int D>
-__device__ __forceinline__ void accumulators_settle(f32x16 (&oacc)[QB][Tile<D>::DB]) {
+__device__ __forceinline__ void accumulators_settle(f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[0][0]));
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+a"(st.l_quad[qb]));
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -433,28 +467,25 @@ __device__ __forceinline__ void qk_only(const unsigned char *lds, int k_off, con
 }
 
 // One instruction's worth (1 KiB per wave) of a tile load.
+// (gbase wave-uniform, off_b the lane's byte offset from it, lds_wave the wave's first LDS byte of the buffer)
 template <int D>
-__device__ __forceinline__ void issue_tile_load_part(const __bf16 *gbase, int off_i, unsigned char *lds, int buf_off,
-                                                     int wave, int i) {
+__device__ __forceinline__ void issue_tile_load_part(const __bf16 *gbase, unsigned off_b, unsigned lds_wave, int i) {
     using T = Tile<D>;
-    lds_direct_load_16(gbase + off_i, lds + buf_off + (RW * wave + T::RPI * i) * (D * 2));
+    lds_direct_load_16_s(gbase, off_b, lds_wave + T::RPI * i * (D * 2));
 }
 
 template <int D>
-__device__ __forceinline__ void issue_vt_load_part(const __bf16 *gbase, int off_i, unsigned char *lds, int buf_off, int wave,
-                                                   int i) {
-    using T = Tile<D>;
-    lds_direct_load_16(gbase + off_i, lds + buf_off + (T::VROWS * wave + 8 * i) * 128);
+__device__ __forceinline__ void issue_vt_load_part(const __bf16 *gbase, unsigned off_b, unsigned lds_wave, int i) {
+    lds_direct_load_16_s(gbase, off_b, lds_wave + 8 * i * 128);
 }
 
 // What the synchronising sub-tile of a tile does besides its arithmetic: wait for this wave's pieces of the next
 // tile, meet the other waves, and request the tile after that.
 template <int D>
 struct TileSync {
-    const __bf16 *kg, *vg;          // global addresses of the first row of the tile to request
-    const LaneOffsets<D> *off;
-    int k_dst, v_dst;               // LDS buffer offsets it goes to
-    int wave;
+    const __bf16 *kg, *vg;          // global addresses (wave-uniform) of the first row of the tile to request
+    const unsigned *k_off, *v_off;  // the lane's byte offsets from them, one per load instruction
+    unsigned k_dst, v_dst;          // LDS byte addresses of this wave's share of the buffers it goes to
 };
 
 // v_max3_f32 without the NaN-quieting self-maxima that fmaxf expands to
@@ -464,97 +495,110 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return x;
 }
 
+// acc += sum of four bf16 weights of this lane, exactly (fp32 accumulation of the rounded values), for one
+// instruction of issue time: the 16-block 4x4x4 MFMA gives lane (block, j) the products of its own four B values with
+// rows of A, and A is all ones, so every one of the four result registers receives the lane's own sum.  The row sums
+// thereby add up exactly the weights that enter P V: O = sum(p v) / sum(p) is normalised by what was multiplied, and a
+// row dominated by one key returns that key's V row up to output rounding.  (Adding the fp32 weights before rounding
+// instead costs four times the issue time and, with outlier keys, output errors above the tolerance;
+// v_dot2c_f32_bf16 on pairs costs eight times the issue time.)
+// Like pv_mfma_raw(), the accumulator stays in accumulation registers whatever the build's default is, and the
+// compiler does not know that this is an MFMA: `ones` must be a register that no VALU instruction has just written
+// (the kernel pins it once), and the packed pairs come from the slot before.
+__device__ __forceinline__ void sum_quad(f32x4 &acc, const u32x2 &ones, unsigned pair0, unsigned pair1) {
+    const u32x2 b = {pair0, pair1};
+    asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(ones), "v"(b));
+}
+// two fp32 weights rounded to bf16, packed (first in the low half)
+__device__ __forceinline__ unsigned pack_pair(float w0, float w1) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 pk = {(__bf16)w0, (__bf16)w1};
+    return __builtin_bit_cast(unsigned, pk);
+}
+
 // One sub-tile (32 keys) of the pipelined loop, written in issue order as a sequence of slots.  A slot is one MFMA
-// plus a slice of independent VALU work and ends with a scheduling fence: a wave issues in order, so VALU work that
-// is not placed between two MFMAs is not overlapped with anything.
-//   slots 0 .. KS*QB-1          s_next = K[next block] Q^T
-//   slots KS*QB .. 2*KS*QB-1    O^T += V^T[this block] P^T
-//   VALU stream, spread over the slots in this order:
-//     E(e)  weight of score e of the current block, p = exp2((s_cur - m_ref) * sl); every second one packs a pair to
-//           bf16 and adds it to the row sum.  First the 16-key half the first P V slots need, then the other half.
-//     R(j)  two scores of s_next leave the accumulators (at least four MFMAs behind the last score MFMA), row max
-// s_cur / sv_next are the scores as plain VGPR values (QB x 16 per lane).  The K operands of this sub-tile arrive in
-// ka (read from LDS during the previous sub-tile), the ones of the following sub-tile are read during the P V slots,
-// and the V operands during the score slots: every LDS read is issued a whole phase before its first use.  With SYNC
-// the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true if
-// some row of the next scores exceeds its reference maximum by more than the threshold.
+// plus a slice of independent VALU work and ends with a scheduling fence.  A wave issues in order and every
+// instruction, MFMA included, occupies the SIMD's one vector issue port (about 5 cycles for a plain VALU instruction,
+// 10 for an exponential, 16 for v_dot2c_f32_bf16, 4 for an MFMA, whose 32 cycles in the matrix pipe run in the
+// background): the loop is bound by the sum of those, so the code below is written to need few instructions.
+//   score slots (KS * QB)         s_next = K[next block] Q^T
+//   P V slots (2 * DB * QB)       O^T += V^T P^T, 16-key half by 16-key half
+//   VALU stream, spread over the slots:
+//     weight e of the current block in stages, F  x = s * sl - m_ref * sl,  X  w = exp2(x),  C  pack a pair to bf16,
+//     L  add four packed weights to the row sum (sum_quad), in consecutive slots (a dependent instruction directly
+//     behind its producer stalls the wave); first the 16-key half the first P V slots need, then the other half;
+//     R(j)  row maximum over two of the next scores (at least four MFMAs behind the last score MFMA), with the
+//     scores clipped to the row's visible key range first when the run is MASKED.
+// The scale stays a multiply per score: folded into Q (rounded to bf16 again) it would perturb a score by 2^-9 of
+// its magnitude, which the outlier-key workload turns into output errors above the tolerance.
+// sv_cur / sv_next are the scores as plain VGPR values (QB x 16 per lane).  K operands: steps 0 .. RING-1 of this
+// sub-tile arrive in ka (read from LDS during the previous sub-tile), the others are read RING steps ahead into the
+// register just used, and so are the V operands: every LDS read is issued at least RING steps before its use.  With
+// SYNC the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true
+// if some lane's next scores exceed its reference maximum by more than the threshold; mx_out holds the lane's maxima
+// (the lane pair of a row is only combined when a raise happens).
 template <int D, bool SYNC, bool MASKED>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
-                                        f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::KS],
-                                        int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st, float sl,
-                                        float (&tmax)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
+                                        f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::RING],
+                                        int k_off, int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
+                                        RowState &st, const u32x2 &ones2, float sl, float raise_margin,
+                                        float (&mx_out)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
                                         const int (&vis_span)[QB] KSA_TRACE_ARG) {
     using T = Tile<D>;
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of the P V phase
     static_assert(NSTEP == T::KS, "one V operand is fetched per score step");
     constexpr int N1 = T::KS * QB;                // score slots
-    constexpr int N2 = NSTEP * QB;                // P V slots
+    constexpr int NH = QB * T::DB;                // P V slots per 16-key half
+    constexpr int N2 = 2 * NH;
     constexpr int NE = QB * 16;                   // weights per lane
-    // The VALU stream is software-pipelined over the slots: a wave issues in order, a dependent VALU instruction
-    // waits several cycles for its operand and a transcendental result some more, so the three stages of a weight
-    //   F  x = s * sl - m_ref * sl        X  w = exp2(x)        C  pack a pair to bf16, add it to the row sum
-    // run in three consecutive slots, and a read-out unit takes its row maximum one slot after its two reads.
-    constexpr int E_SLOTS = N1 + N2 / 2 - 2;      // slots that start a weight; the last C stage ends before slot N1 + N2 / 2
-    constexpr int R_FIRST = N1 + (N2 >= 8 ? 4 : 2);   // first slot that may read s_next (its last MFMA is two or more MFMAs back)
+    constexpr int E_SLOTS = N1 + NH - 3;          // slots that start a weight: the last C stage sits two slots before slot
+                                                  // N1 + NH (a raw MFMA must not read a register a VALU instruction has
+                                                  // only just written)
+    constexpr int R_FIRST = N1 + 4;               // first slot that may read sv_next (four MFMAs behind its last MFMA)
     constexpr int R_SLOTS = N1 + N2 - 1 - R_FIRST;
-    constexpr int NR = QB * 8;                    // read-out units (two scores each)
+    constexpr int NR = QB * 8;                    // row-maximum units (two scores each)
     static_assert(E_SLOTS >= 1 && R_SLOTS >= 1, "the phases are too short for the pipelined VALU stream");
+    static_assert((NE / 2 - 1) * E_SLOTS / NE + 2 <= N1 - 2, "the first half's weights are not packed in time");
+    static_assert(E_SLOTS - 1 + 4 <= N1 + N2 - 1, "the last row-sum step does not fit into the sub-tile");
     static_assert(1 + T::NI + T::NIV <= N2, "the tile requests do not fit into the P V slots");
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    const int lv = (ll.vt ^ (sb << 6)) + v_off, lkn = ll.k + k_next_off;
-    float msl[QB], rsum[QB], mx[QB];
+    constexpr int RING = T::RING;                 // operands in flight per kind
+    const int lk = ll.k + k_off, lv = (ll.vt ^ (sb << 6)) + v_off, lkn = ll.k + k_next_off;
+    float msl[QB], mx[QB];
+    int mask_base[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         msl[qb] = st.m_ref[qb] * sl;
-        rsum[qb] = st.l_part[qb];
         mx[qb] = -INFINITY;
+        mask_base[qb] = MASKED ? next_key0 - vis_lo[qb] : 0;
     }
-    int mask_base[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) mask_base[qb] = MASKED ? next_key0 - vis_lo[qb] : 0;
-    bf16x8 p[QB][2];
-    bf16x8 va[NSTEP];
+    u32x4 p[QB][2];                               // packed weight pairs: the B operand of P V
+    bf16x8 va[RING];
     float xs[NE], ws[NE];
-    // weight e = hf * (QB * 8) + qb * 8 + i  ->  score register 8 * hf + i of query block qb;
-    // first the 16-key half (hf = 0) that the first P V slots need
+    // weight e = hf * (QB * 8) + qb * 8 + i  ->  score register 8 * hf + i of query block qb
     auto slot_of_e = [](int e) { return e * E_SLOTS / NE; };
     auto slot_of_r = [](int j) { return R_FIRST + j * R_SLOTS / NR; };
     auto valu_slice = [&](int u) {
-#if defined(KSA_ABL) && (KSA_ABL & 1)
-        if (u == 0) { for (int q2 = 0; q2 < QB; ++q2) for (int h2 = 0; h2 < 2; ++h2) for (int i2 = 0; i2 < 8; ++i2) p[q2][h2][i2] = (__bf16)0.5f; }
-        return;
-#endif
-#if defined(KSA_ABL) && (KSA_ABL & 16)
-        if (u == 0) { for (int q2 = 0; q2 < QB; ++q2) for (int h2 = 0; h2 < 2; ++h2) for (int i2 = 0; i2 < 8; ++i2) p[q2][h2][i2] = (__bf16)0.5f; }
-#else
 #pragma unroll
         for (int e = 1; e < NE; e += 2)
             if (slot_of_e(e) + 2 == u) {   // C
                 const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
-                bf16x2 pk;
-                pk[0] = (__bf16)ws[e - 1];
-                pk[1] = (__bf16)ws[e];
-                rsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, rsum[qb], false);
-                asm volatile("" : "+v"(rsum[qb]));   // keeps the sum in this slot instead of at the end of the block
-                p[qb][hf][i - 1] = pk[0];
-                p[qb][hf][i] = pk[1];
+                p[qb][hf][i / 2] = pack_pair(ws[e - 1], ws[e]);
             }
+        // exponentials and multiply-adds alternate: a transcendental keeps its unit busy for several issue slots
 #pragma unroll
-        for (int e = 0; e < NE; ++e)
+        for (int e = 0; e < NE; ++e) {
             if (slot_of_e(e | 1) + 1 == u) {   // X (both weights of a pair in the slot of the odd one)
                 ws[e] = __builtin_amdgcn_exp2f(xs[e]);
                 asm volatile("" : "+v"(ws[e]));
+                KSA_STEP_FENCE();
             }
-#pragma unroll
-        for (int e = 0; e < NE; ++e)
             if (slot_of_e(e | 1) == u) {   // F
                 const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
                 xs[e] = fmaf(sv_cur[qb][8 * hf + i], sl, -msl[qb]);
                 asm volatile("" : "+v"(xs[e]));
+                KSA_STEP_FENCE();
             }
-#endif
-#if !(defined(KSA_ABL) && (KSA_ABL & 8))
+        }
 #pragma unroll
         for (int j = 0; j < NR; ++j)
             if (slot_of_r(j) == u) {
@@ -570,7 +614,16 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                 }
                 mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
             }
-#endif
+        // L last: the matrix pipe takes one MFMA at a time and a wave that issues a second one waits for it, so the
+        // small MFMA goes where the slot's big one has (nearly) drained, right in front of the next slot's.  Two slots
+        // behind the pack: a raw MFMA must not read a register that a VALU instruction has only just written.
+#pragma unroll
+        for (int e = 3; e < NE; e += 4)
+            if (slot_of_e(e) + 4 == u) {
+                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
+                KSA_STEP_FENCE();
+                sum_quad(st.l_quad[qb], ones2, p[qb][hf][i / 2 - 1], p[qb][hf][i / 2]);
+            }
     };
 #ifdef KSA_TRACE
     const unsigned long long T0 = KSA_NOW();
@@ -580,15 +633,17 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
 #pragma unroll
     for (int u = 0; u < N1; ++u) {
         const int sk = u / QB, qb = u % QB;
-#if defined(KSA_ABL) && (KSA_ABL & 2)
-        if (qb == 0) va[sk] = ka[sk];
-#else
-        if (qb == 0) va[sk] = read_vt_operand(lds, lv, sk / T::DB, sk % T::DB);   // needed a whole phase from now
-#endif
         if (sk == 0)
-            score_mfma_first(sv_next[qb], ka[sk], qreg[qb][sk]);
+            score_mfma_first(sv_next[qb], ka[sk % RING], qreg[qb][sk]);
         else
-            score_mfma_next(sv_next[qb], ka[sk], qreg[qb][sk]);
+            score_mfma_next(sv_next[qb], ka[sk % RING], qreg[qb][sk]);
+        if (qb == QB - 1) {
+            if (sk + RING < T::KS) ka[sk % RING] = read_k_operand<D>(lds, lk, sk + RING);
+            if (sk >= T::KS - RING) {
+                const int x = sk - (T::KS - RING);
+                va[x] = read_vt_operand(lds, lv, x / T::DB, x % T::DB);
+            }
+        }
         valu_slice(u);
         KSA_STEP_FENCE();
     }
@@ -602,7 +657,9 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
     for (int u = 0; u < N2; ++u) {
         const int x = u / QB, qb = u % QB;
         const int hf = x / T::DB, db = x % T::DB;
-        pv_mfma_raw(oacc[qb][db], va[x], p[qb][hf]);
+        pv_mfma_raw(oacc[qb][db], va[x % RING], p[qb][hf]);
+        // the V operand RING steps ahead goes into the register this step has just used
+        if (qb == QB - 1 && x + RING < NSTEP) va[x % RING] = read_vt_operand(lds, lv, (x + RING) / T::DB, (x + RING) % T::DB);
         if (SYNC) {
             if (u == 0) {
 #ifdef KSA_TRACE
@@ -620,36 +677,31 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
 #endif
             }
             // the tile after next, one instruction per slot
-#if !(defined(KSA_ABL) && (KSA_ABL & 4))
-            if (u >= 1 && u - 1 < T::NI)
-                issue_tile_load_part<D>(sync.kg, sync.off->k[u - 1], lds, sync.k_dst, sync.wave, u - 1);
+            if (u >= 1 && u - 1 < T::NI) issue_tile_load_part<D>(sync.kg, sync.k_off[u - 1], sync.k_dst, u - 1);
             if (u >= 1 + T::NI && u - 1 - T::NI < T::NIV)
-                issue_vt_load_part<D>(sync.vg, sync.off->vt[u - 1 - T::NI], lds, sync.v_dst, sync.wave, u - 1 - T::NI);
-#endif
+                issue_vt_load_part<D>(sync.vg, sync.v_off[u - 1 - T::NI], sync.v_dst, u - 1 - T::NI);
         }
-#if !(defined(KSA_ABL) && (KSA_ABL & 2))
-        if (qb == QB - 1) ka[x] = read_k_operand<D>(lds, lkn, x);   // K operands of the following sub-tile
-#endif
+        // the first RING K operands of the following sub-tile, in the second half of the slots
+#pragma unroll
+        for (int x = 0; x < RING; ++x)
+            if (NH + x * NH / RING == u) ka[x] = read_k_operand<D>(lds, lkn, x);
         if (N1 + u == R_FIRST) {
             // from here on the next scores may be read
 #pragma unroll
             for (int q2 = 0; q2 < QB; ++q2) scores_ready(sv_next[q2]);
         }
         valu_slice(N1 + u);
-        if (u == N2 - 1) {
-#pragma unroll
-            for (int q2 = 0; q2 < QB; ++q2) tmax[q2] = max3(mx[q2], mx[q2], other_half(mx[q2]));
-        }
         KSA_STEP_FENCE();
     }
 #ifdef KSA_TRACE
     tr.acc[SYNC ? 3 : 5] += KSA_NOW() - T3;
 #endif
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) st.l_part[qb] = rsum[qb];
     bool raise = false;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+    for (int qb = 0; qb < QB; ++qb) {
+        mx_out[qb] = mx[qb];
+        raise |= mx[qb] > st.m_ref[qb] + raise_margin;   // (mx - m_ref) * sl > threshold
+    }
     return __builtin_amdgcn_ballot_w64(raise) != 0;
 }
 
@@ -742,6 +794,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     for (int qb = 0; qb < QB; ++qb) {
         st.m_ref[qb] = -1e30f;
         st.l_part[qb] = 0.f;
+        st.l_quad[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
@@ -750,7 +803,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
 
     const __bf16 *kbase = a.k + b * a.ks[0] + hkv * a.ks[2];
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
+    // four bf16 ones, the A operand of sum_quad(); opaque from here on: a constant would be re-materialised by VALU moves
+    // right in front of the raw MFMAs that read it, and the compiler inserts no wait states for those
+    u32x2 ones2 = {0x3f803f80u, 0x3f803f80u};
+    asm volatile("" : "+v"(ones2));
     const float sl = a.scale_log2e;
+    const float raise_margin = RESCALE_THRESHOLD_LOG2 / sl;   // the rescale threshold in raw score units
 
 #ifdef KSA_TRACE
     tr.acc[14] = KSA_NOW() - TK0;
@@ -785,9 +843,20 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             const __bf16 *vtbase = a.vt + (space == KSA_SPACE_TEXT ? 0 : a.vt_sum_off) +
                                    ((int64_t)(b * a.n_kv_heads + hkv) * D) * vt_stride + seg_begin;
             lane_offsets_vt<D>(vt_stride, wave, lane, off);
-            auto issue_vt_tile = [&](int t, int buf_off) {
+            // the lane's byte offsets from the wave-uniform tile addresses, and the wave's share of an LDS buffer
+            unsigned k_offb[T::NI], v_offb[T::NIV];
 #pragma unroll
-                for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(vtbase + t * BN, off.vt[i], lds, buf_off, wave, i);
+            for (int i = 0; i < T::NI; ++i) k_offb[i] = (unsigned)off.k[i] * 2u;
+#pragma unroll
+            for (int i = 0; i < T::NIV; ++i) v_offb[i] = (unsigned)off.vt[i] * 2u;
+            const unsigned lds0 = (unsigned)(size_t)lds;
+            const unsigned k_wave = lds0 + K0 + RW * wave * (D * 2), v_wave = lds0 + V0 + T::VROWS * wave * 128;
+            auto issue_tile = [&](int t, int buf_off) {
+                const __bf16 *kg = kbase + tile_base(t), *vg = vtbase + t * BN;
+#pragma unroll
+                for (int i = 0; i < T::NI; ++i) issue_tile_load_part<D>(kg, k_offb[i], k_wave + buf_off, i);
+#pragma unroll
+                for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(vg, v_offb[i], v_wave + buf_off, i);
             };
             // visible key range of each of the lane's rows inside this run: [lo, lo + span), lo stored minus 4 * h
             int vis_lo[QB], vis_span[QB];
@@ -802,14 +871,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 constexpr bool MASKED = decltype(masked_tag)::value;
                 const int second = n_tiles > 1 ? 1 : 0;
                 __syncthreads();                     // earlier readers of the LDS buffers are done
-                issue_tile_load<D>(kbase + tile_base(0), off.k, lds, K0, wave);
-                issue_vt_tile(0, V0);
-                issue_tile_load<D>(kbase + tile_base(second), off.k, lds, K0 + T::BYTES, wave);
-                issue_vt_tile(second, V0 + T::BYTES);
+                issue_tile(0, 0);
+                issue_tile(second, T::BYTES);
                 __builtin_amdgcn_s_waitcnt(0);
                 __syncthreads();
                 f32x16 sv_a[QB], sv_b[QB];
-                float tmax[QB];
+                float mxl[QB];                       // the lane's maxima of the pending scores
                 bool raise = false;
                 qk_only<D>(lds, K0, ll, qreg, sv_a);
 #pragma unroll
@@ -826,17 +893,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     float mx = -INFINITY;
 #pragma unroll
                     for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
-                    tmax[qb] = max3(mx, mx, other_half(mx));
-                    raise |= (tmax[qb] - st.m_ref[qb]) * sl > RESCALE_THRESHOLD_LOG2;
+                    mxl[qb] = mx;
+                    raise |= mx > st.m_ref[qb] + raise_margin;
                 }
                 raise = __builtin_amdgcn_ballot_w64(raise) != 0;
-                bf16x8 ka_pre[T::KS];
+                bf16x8 ka_pre[T::RING];
 #pragma unroll
-                for (int s = 0; s < T::KS; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
+                for (int s = 0; s < T::RING; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
                 int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
                 TileSync<D> sync;
-                sync.off = &off;
-                sync.wave = wave;
+                sync.k_off = k_offb;
+                sync.v_off = v_offb;
 #ifdef KSA_TRACE
                 const unsigned long long TL0 = KSA_NOW();
                 tr.acc[12] += TL0 - TS0;
@@ -851,43 +918,27 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     const int t_ld = t + 2 < n_tiles ? t + 2 : n_tiles - 1;
                     sync.kg = kbase + tile_base(t_ld);
                     sync.vg = vtbase + t_ld * BN;
-                    sync.k_dst = K0 + b_ld;
-                    sync.v_dst = V0 + b_ld;
+                    sync.k_dst = k_wave + b_ld;
+                    sync.v_dst = v_wave + b_ld;
                     const int key0 = seg_begin + t * BN;
-#if defined(KSA_DBG_SYNC) && (KSA_DBG_SYNC & 1)
-                    __syncthreads();
-#endif
                     // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
-#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 1)
-                    raise = true;
-#endif
-#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
-                    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#endif
-                    if (raise) raise_reference<D, true>(st, tmax, oacc, sl);
-                    raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, V0 + b_cur, 0, K0 + b_nxt, oacc, st, sl, tmax,
-                                                     sync, key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
-#if defined(KSA_DBG_SYNC) && (KSA_DBG_SYNC & 2)
-                    __syncthreads();
-#endif
+                    if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                    raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, 0,
+                                                     K0 + b_nxt, oacc, st, ones2, sl, raise_margin, mxl, sync, key0 + 32, vis_lo,
+                                                     vis_span KSA_TRACE_PASS);
                     // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
                     // (for the last tile those scores come from a buffer that holds no new tile and are never used)
-#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 2)
-                    raise = true;
-#endif
-#if defined(KSA_DBG_ALWAYS_RAISE) && (KSA_DBG_ALWAYS_RAISE & 4)
-                    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#endif
-                    if (raise) raise_reference<D, true>(st, tmax, oacc, sl);
-                    raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, V0 + b_cur, 1, K0 + b_nxt + HALF, oacc, st, sl,
-                                                      tmax, sync, key0 + BN, vis_lo, vis_span KSA_TRACE_PASS) &&
+                    if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                    raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur, 1,
+                                                      K0 + b_nxt + HALF, oacc, st, ones2, sl, raise_margin, mxl, sync, key0 + BN,
+                                                      vis_lo, vis_span KSA_TRACE_PASS) &&
                             (t + 1 < n_tiles);
                     const int b_old = b_cur;
                     b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
                 }
                 // the request repeated for the last tile is still in flight: let it land before anyone reuses LDS
                 __builtin_amdgcn_s_waitcnt(0x0F70);
-                accumulators_settle<D>(oacc);
+                accumulators_settle<D>(oacc, st);
 #ifdef KSA_TRACE
                 tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TL0;
                 tr.acc[MASKED ? 15 : 6] += n_tiles;
@@ -932,7 +983,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             }
             bf16x8 pb[QB][2][2];
             float tmax[QB];
-            if (tile_max(sacc, st, sl, tmax)) raise_reference<D, false>(st, tmax, oacc, sl);
+            if (tile_max(sacc, st, sl, tmax)) raise_reference<D>(st, tmax, oacc, sl);
             exp_and_pack(sacc, pb, st, sl);
             pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
@@ -951,7 +1002,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float l_row = st.l_part[qb] + other_half(st.l_part[qb]);
+        const float l_lane = PIPELINED ? st.l_quad[qb][0] : st.l_part[qb];
+        const float l_row = l_lane + other_half(l_lane);
         if (!q_valid[qb]) continue;
         const float inv = 1.0f / l_row;
         __bf16 *op = a.o + b * a.os[0] + (int64_t)q_aug[qb] * a.os[1] + hq * a.os[2];
@@ -1080,6 +1132,8 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     {
         const int64_t period = a.m > 0 && a.m < a.c ? a.m : a.c;
         if (L.kv_strides[1] * ((BN / period + 2) * (int64_t)a.w) >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
+        // ... and so are the ones into the key-major copy of V (head_dim rows of nt_pad or ns_pad keys)
+        if ((int64_t)L.p.head_dim * (a.nt_pad > a.ns_pad ? a.nt_pad : a.ns_pad) >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (L.phases & 1) {

@@ -168,6 +168,47 @@ def test_prefill_128k_sampled_rows():
     sampled_compare(synth.CONFIGS["prefill_128k"], n_random=160)
 
 
+def expected_key_major_v(cfg, v):
+    """The workspace ksa_prefill_relayout_v writes, from its definition: per index space (text, then summaries) an
+    array [B, Hkv, d, keys padded to 64] with
+        vt[d][64 t + 8 pc + e] = V[key 64 t + 32 sb + 16 hf + 8 (e / 4) + 4 h + e % 4][d],  pc = 4 sb + 2 hf + h,
+    keys counted in the compact index of the space (text index i is augmented row (i / c)(c + m) + i % c, summary
+    index u is (u / m)(c + m) + c + u % m), zeros past the end of the space."""
+    c, m = cfg.chunk_len, cfg.n_summary
+    vb = v.view(torch.int16).numpy()                         # [B, L, Hkv, d] bit patterns
+    B, L, H, d = vb.shape
+    parts = []
+    for n_keys, aug in ((cfg.n_text, lambda i: (i // c) * (c + m) + i % c),
+                        ((cfg.n_text // c) * m, lambda u: (u // m) * (c + m) + c + u % m)):
+        pad = (n_keys + 63) // 64 * 64
+        if pad == 0:
+            continue
+        out = np.zeros((B, H, d, pad), dtype=np.int16)
+        pos = np.arange(pad)
+        t, pc, e = pos // 64, (pos % 64) // 8, pos % 8
+        key = 64 * t + 32 * (pc // 4) + 16 * ((pc // 2) % 2) + 8 * (e // 4) + 4 * (pc % 2) + e % 4
+        ok = key < n_keys
+        rows = aug(key[ok])
+        out[:, :, :, ok] = vb[:, rows].transpose(0, 2, 3, 1)   # [B, keys, H, d] -> [B, H, d, keys]
+        parts.append(out.reshape(-1))
+    return np.concatenate(parts)
+
+
+@pytest.mark.parametrize("name", ["tiny", "prefill_4k"])
+def test_relayout_v_is_the_documented_permutation(name):
+    cfg = synth.CONFIGS[name]
+    say(f"relayout_v {cfg.name}")
+    _, _, v = synth.make_prefill_inputs(cfg)
+    lay = K.ksa_build_layout(params_of(cfg))
+    ws = torch.full((K.prefill_workspace_bytes(lay),), 0x5A, dtype=torch.uint8, device="cuda")
+    K.ksa_prefill_relayout_v(lay, v.cuda(), ws)
+    torch.cuda.synchronize()
+    got = ws.cpu().numpy().view(np.int16)
+    want = expected_key_major_v(cfg, v)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
 def test_repeatable():
     cfg = synth.CONFIGS["prefill_4k"]
     q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
