@@ -279,7 +279,7 @@ __device__ __forceinline__ void pv_mfma(const unsigned char *lds, int buf_off, c
 // the end).
 struct RowState {
     float m_ref[QB], l_part[QB];
-    f32x4 l_quad[QB];   // pipelined kernel: the lane's part of the row sum, kept by sum_quad() (register 0 is read)
+    f32x4 l_sum[QB];    // pipelined kernel: row sums kept by sum_half(): lanes 0..15, registers 0 (query = lane) and 1 (+ 16)
 };
 
 // Row maxima of a score tile; returns true if some lane's row exceeds its reference by more than the threshold.
@@ -335,12 +335,15 @@ __device__ __forceinline__ void raise_reference_pl(RowState &st, const float (&m
         // (old - new) first: equal references (also the -1e30 start value) must give exactly 2^0
         const float alpha = __builtin_amdgcn_exp2f((st.m_ref[qb] - m_new) * sl);
         st.m_ref[qb] = m_new;
-        {   // the row sum: register 0 is the one that is read
-            float acc = st.l_quad[qb][0], tmp;
+        // the row sums: lane j < 16 holds query j in register 0 and query j + 16 in register 1
+        const float alpha_hi = __shfl(alpha, (threadIdx.x & 15) + 16);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float acc = st.l_sum[qb][i], tmp;
             asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
                          : "+a"(acc), "=&v"(tmp)
-                         : "v"(alpha));
-            st.l_quad[qb][0] = acc;
+                         : "v"(i == 0 ? alpha : alpha_hi));
+            st.l_sum[qb][i] = acc;
         }
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
@@ -371,7 +374,7 @@ template <int D>
 __device__ __forceinline__ void accumulators_settle(f32x16 (&oacc)[QB][Tile<D>::DB], RowState &st) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(oacc[0][0]));
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+a"(st.l_quad[qb]));
+    for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+a"(st.l_sum[qb]));
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -495,19 +498,21 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return x;
 }
 
-// acc += sum of four bf16 weights of this lane, exactly (fp32 accumulation of the rounded values), for one
-// instruction of issue time: the 16-block 4x4x4 MFMA gives lane (block, j) the products of its own four B values with
-// rows of A, and A is all ones, so every one of the four result registers receives the lane's own sum.  The row sums
-// thereby add up exactly the weights that enter P V: O = sum(p v) / sum(p) is normalised by what was multiplied, and a
-// row dominated by one key returns that key's V row up to output rounding.  (Adding the fp32 weights before rounding
-// instead costs four times the issue time and, with outlier keys, output errors above the tolerance;
-// v_dot2c_f32_bf16 on pairs costs eight times the issue time.)
-// Like pv_mfma_raw(), the accumulator stays in accumulation registers whatever the build's default is, and the
-// compiler does not know that this is an MFMA: `ones` must be a register that no VALU instruction has just written
-// (the kernel pins it once), and the packed pairs come from the slot before.
-__device__ __forceinline__ void sum_quad(f32x4 &acc, const u32x2 &ones, unsigned pair0, unsigned pair1) {
-    const u32x2 b = {pair0, pair1};
-    asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(ones), "v"(b));
+// Row sums by the matrix unit: acc(16x16) += A(16x32) P^T(32x16) with the eight packed weights of one 16-key half as
+// the B operand, exactly as they enter P V.  As B of the 16x16x32 MFMA, lane l supplies column l % 16, k group l / 16;
+// the lanes of column j are j, j + 16, j + 32, j + 48, which hold the weights of query j (lane halves 0 and 1: groups
+// 0 and 2) and of query j + 16 (groups 1 and 3).  A is an indicator matrix: row 0 is one on groups 0 and 2, row 1 on
+// groups 1 and 3, all else zero (`ind`: all ones in lanes 0, 32, 17 and 49).  Result: lane j < 16 holds in register 0
+// the sum over all sixteen weights of query j, in register 1 that of query j + 16, in fp32, of the ROUNDED weights, so
+// O = sum(p v) / sum(p) is normalised by what was multiplied and a row dominated by one key returns that key's V row
+// up to output rounding.  (Adding the fp32 weights before rounding costs more issue time and, with outlier keys, output
+// errors above the tolerance; v_dot2c_f32_bf16 on pairs costs 16 cycles of issue per pair; the 4x4x4 MFMA sums only
+// four weights for the same 16 cycles in the matrix pipe.)
+// Like pv_mfma_raw(), the accumulator stays in accumulation registers and the compiler does not know that this is an
+// MFMA: `ind` must be a register that no VALU instruction has just written (the kernel pins it once), and the packed
+// weights come from two slots before.
+__device__ __forceinline__ void sum_half(f32x4 &acc, const u32x4 &ind, const u32x4 &p_op) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(ind), "v"(p_op));
 }
 // two fp32 weights rounded to bf16, packed (first in the low half)
 __device__ __forceinline__ unsigned pack_pair(float w0, float w1) {
@@ -525,7 +530,7 @@ __device__ __forceinline__ unsigned pack_pair(float w0, float w1) {
 //   P V slots (2 * DB * QB)       O^T += V^T P^T, 16-key half by 16-key half
 //   VALU stream, spread over the slots:
 //     weight e of the current block in stages, F  x = s * sl - m_ref * sl,  X  w = exp2(x),  C  pack a pair to bf16,
-//     L  add four packed weights to the row sum (sum_quad), in consecutive slots (a dependent instruction directly
+//     L  add a packed 16-key half to the row sums (sum_half), in consecutive slots (a dependent instruction directly
 //     behind its producer stalls the wave); first the 16-key half the first P V slots need, then the other half;
 //     R(j)  row maximum over two of the next scores (at least four MFMAs behind the last score MFMA), with the
 //     scores clipped to the row's visible key range first when the run is MASKED.
@@ -541,7 +546,7 @@ template <int D, bool SYNC, bool MASKED>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
                                         f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::RING],
                                         int k_off, int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
-                                        RowState &st, const u32x2 &ones2, float sl, float raise_margin,
+                                        RowState &st, const u32x4 &ind, float sl, float raise_margin,
                                         float (&mx_out)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
                                         const int (&vis_span)[QB] KSA_TRACE_ARG) {
     using T = Tile<D>;
@@ -578,13 +583,7 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
     auto slot_of_e = [](int e) { return e * E_SLOTS / NE; };
     auto slot_of_r = [](int j) { return R_FIRST + j * R_SLOTS / NR; };
     auto valu_slice = [&](int u) {
-#pragma unroll
-        for (int e = 1; e < NE; e += 2)
-            if (slot_of_e(e) + 2 == u) {   // C
-                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
-                p[qb][hf][i / 2] = pack_pair(ws[e - 1], ws[e]);
-            }
-        // exponentials and multiply-adds alternate: a transcendental keeps its unit busy for several issue slots
+        // exponentials and multiply-adds first, alternating: a transcendental keeps its unit busy for several issue slots
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             if (slot_of_e(e | 1) + 1 == u) {   // X (both weights of a pair in the slot of the odd one)
@@ -599,6 +598,23 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                 KSA_STEP_FENCE();
             }
         }
+        // L in the middle of the slot: the matrix pipe takes one MFMA at a time and a wave that issues one while the
+        // pipe is busy waits for it, so the small MFMA sits about 30 cycles of VALU work behind the slot's big MFMA and
+        // has 10 to 20 cycles of VALU work between itself and the next slot's.  Two slots behind the pack: a raw MFMA
+        // must not read a register that a VALU instruction has only just written.
+#pragma unroll
+        for (int e = 7; e < NE; e += 8)
+            if (slot_of_e(e) + 4 == u) {
+                const int hf = e / (QB * 8), qb = (e / 8) % QB;
+                sum_half(st.l_sum[qb], ind, p[qb][hf]);
+                KSA_STEP_FENCE();
+            }
+#pragma unroll
+        for (int e = 1; e < NE; e += 2)
+            if (slot_of_e(e) + 2 == u) {   // C
+                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
+                p[qb][hf][i / 2] = pack_pair(ws[e - 1], ws[e]);
+            }
 #pragma unroll
         for (int j = 0; j < NR; ++j)
             if (slot_of_r(j) == u) {
@@ -613,16 +629,6 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                     }
                 }
                 mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
-            }
-        // L last: the matrix pipe takes one MFMA at a time and a wave that issues a second one waits for it, so the
-        // small MFMA goes where the slot's big one has (nearly) drained, right in front of the next slot's.  Two slots
-        // behind the pack: a raw MFMA must not read a register that a VALU instruction has only just written.
-#pragma unroll
-        for (int e = 3; e < NE; e += 4)
-            if (slot_of_e(e) + 4 == u) {
-                const int hf = e / (QB * 8), qb = (e / 8) % QB, i = e % 8;
-                KSA_STEP_FENCE();
-                sum_quad(st.l_quad[qb], ones2, p[qb][hf][i / 2 - 1], p[qb][hf][i / 2]);
             }
     };
 #ifdef KSA_TRACE
@@ -794,7 +800,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     for (int qb = 0; qb < QB; ++qb) {
         st.m_ref[qb] = -1e30f;
         st.l_part[qb] = 0.f;
-        st.l_quad[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.l_sum[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < T::DB; ++db)
 #pragma unroll
@@ -803,10 +809,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
 
     const __bf16 *kbase = a.k + b * a.ks[0] + hkv * a.ks[2];
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
-    // four bf16 ones, the A operand of sum_quad(); opaque from here on: a constant would be re-materialised by VALU moves
-    // right in front of the raw MFMAs that read it, and the compiler inserts no wait states for those
-    u32x2 ones2 = {0x3f803f80u, 0x3f803f80u};
-    asm volatile("" : "+v"(ones2));
+    // the A operand of sum_half(); opaque from here on: a value the compiler can see through would be re-materialised by
+    // VALU moves right in front of the raw MFMAs that read it, and the compiler inserts no wait states for those
+    const unsigned ind1 = (lane == 0 || lane == 32 || lane == 17 || lane == 49) ? 0x3f803f80u : 0u;
+    u32x4 ind = {ind1, ind1, ind1, ind1};
+    asm volatile("" : "+v"(ind));
     const float sl = a.scale_log2e;
     const float raise_margin = RESCALE_THRESHOLD_LOG2 / sl;   // the rescale threshold in raw score units
 
@@ -924,13 +931,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
                     if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                     raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, 0,
-                                                     K0 + b_nxt, oacc, st, ones2, sl, raise_margin, mxl, sync, key0 + 32, vis_lo,
+                                                     K0 + b_nxt, oacc, st, ind, sl, raise_margin, mxl, sync, key0 + 32, vis_lo,
                                                      vis_span KSA_TRACE_PASS);
                     // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
                     // (for the last tile those scores come from a buffer that holds no new tile and are never used)
                     if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                     raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur, 1,
-                                                      K0 + b_nxt + HALF, oacc, st, ones2, sl, raise_margin, mxl, sync, key0 + BN,
+                                                      K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl, sync, key0 + BN,
                                                       vis_lo, vis_span KSA_TRACE_PASS) &&
                             (t + 1 < n_tiles);
                     const int b_old = b_cur;
@@ -1002,8 +1009,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float l_lane = PIPELINED ? st.l_quad[qb][0] : st.l_part[qb];
-        const float l_row = l_lane + other_half(l_lane);
+        float l_row;
+        if (PIPELINED) {   // lane j < 16 holds the sums of queries j (register 0) and j + 16 (register 1)
+            const float s0 = __shfl(st.l_sum[qb][0], r & 15), s1 = __shfl(st.l_sum[qb][1], r & 15);
+            l_row = (r & 16) ? s1 : s0;
+        } else {
+            l_row = st.l_part[qb] + other_half(st.l_part[qb]);
+        }
         if (!q_valid[qb]) continue;
         const float inv = 1.0f / l_row;
         __bf16 *op = a.o + b * a.os[0] + (int64_t)q_aug[qb] * a.os[1] + hq * a.os[2];
