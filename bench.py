@@ -182,9 +182,39 @@ def main():
                             "traffic": measured_traffic("decode")},
     }
 
+    out["cache_lifecycle"] = cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
     print(json.dumps(out), flush=True)
+
+
+def cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args):
+    """Not part of the timed step: the data-movement entry points of the decode loop and its summary-token step,
+    timed with events at the benchmark shapes (hand-off of the 128K prefill; one insert and one summary step of
+    the B = 64 decode workload)."""
+    import torch
+    import paper_2604_24432_amd as K
+    s_cap, rows = K.cache_geometry(p)
+    hk = torch.empty((cfg.batch, cfg.n_kv_heads, rows, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    hv = torch.empty_like(hk)
+    fill_ms = time_events(lambda: K.ksa_cache_from_prefill(p, cfg.n_text, k, v, hk, hv), args.steps)
+    moved_rows = s_cap + min(cfg.n_text // cfg.chunk_len, cfg.window_chunks + 1) * cfg.chunk_len
+    fill_bytes = 2.0 * 2.0 * cfg.batch * cfg.n_kv_heads * moved_rows * cfg.head_dim * 2   # K and V, read + written
+    k_new = torch.randn((dcfg.batch, dcfg.n_kv_heads, dcfg.head_dim), device="cuda").to(torch.bfloat16)
+    v_new = torch.randn_like(k_new)
+    d_s_cap, _ = K.cache_geometry(dp)
+    pos_t = torch.full((dcfg.batch,), dcfg.decode_pos, dtype=torch.int32, device="cuda")
+    ord_t = torch.full((dcfg.batch,), d_s_cap - 1, dtype=torch.int32, device="cuda")
+    do = torch.empty_like(dq)
+    app_ms = time_events(lambda: K.ksa_cache_append(dp, K.KSA_ROW_TEXT, k_new, v_new, pos_t, k_cache, v_cache), args.steps)
+    sum_ms = time_events(lambda: K.ksa_decode_summary_fwd(dp, dq, k_cache, v_cache, ord_t, o=do, return_lse=False,
+                                                           workspace=ws, n_splits=args.decode_splits), args.steps)
+    fill_avg = float(np.mean(fill_ms))
+    return {"cache_from_prefill_ms": round(fill_avg, 5), "cache_from_prefill_bytes": fill_bytes,
+            "cache_from_prefill_gbs": round(fill_bytes / (fill_avg * 1e-3) / 1e9, 1),
+            "cache_append_ms": round(float(np.mean(app_ms)), 5),
+            "decode_summary_fwd_ms": round(float(np.mean(sum_ms)), 5),
+            "note": "hand-off of the 128K prefill (B1); insert and summary step at the decode shape (B64)"}
 
 
 def cpu_baseline(cfg, q, k, v, o_gpu, flops_per_pair_all_heads):

@@ -188,6 +188,58 @@ int ksa_decode_fwd(const ksa_params *params /*host*/, const void *q, const void 
                    const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
                    size_t workspace_bytes, int32_t n_splits, void *stream);
 
+/* ---- cache lifecycle of the decode loop (section 2.3.1, the step-by-step cache description) ----------- */
+
+/* Kind of a row / of a query in the calls below. */
+#define KSA_ROW_TEXT 0     /* a text token; its position argument is a text index i in [0, n_text)            */
+#define KSA_ROW_SUMMARY 1  /* a summary token; its position argument is a summary ordinal u = j*m + slot      */
+
+/*
+ * ksa_cache_from_prefill: hand-off from a prefilled sequence to the decode loop.  k, v: device bf16
+ * [B, L, Hkv, d], the augmented sequence of n_prefill text tokens (n_prefill a multiple of chunk_len, at most
+ * params->n_text; L = (n_prefill / c)(c + m)), kv_strides = {batch, row, head} in elements (NULL = contiguous).
+ * Writes, per (batch, KV head), the summaries of all n_prefill / c chunks into the Summary Token Buffer and the
+ * text of the last min(n_prefill / c, C + 1) chunks into the text ring of k_cache, v_cache (geometry above,
+ * cache_strides = {batch, head, row}, NULL = contiguous).  Other cache rows are left as they are.  The next
+ * token of every sequence is then text index n_prefill.  params->n_text is the capacity of the cache.
+ * n_prefill = 0 is a no-op (k and v may be NULL then).
+ * Errors: INVALID_ARG (null or misaligned pointers, n_prefill not a non-negative multiple of chunk_len,
+ * strides not multiples of 8), OUT_OF_RANGE (n_prefill > n_text), HIP.
+ */
+int ksa_cache_from_prefill(const ksa_params *params /*host*/, int64_t n_prefill, const void *k, const void *v,
+                           const int64_t kv_strides[3], void *k_cache, void *v_cache,
+                           const int64_t cache_strides[3], void *stream);
+
+/*
+ * ksa_cache_append: one new row per sequence.  k_new, v_new: device bf16 [B, Hkv, d] contiguous.
+ * kind = KSA_ROW_TEXT: pos[b] (device int32 [B]) is the text index of the token; its row goes into the slot of the
+ * current chunk in the ring, over the row of the chunk that left the window C + 1 chunks ago (the paper's insert
+ * and evict steps in one store).  kind = KSA_ROW_SUMMARY: pos[b] is the summary ordinal j*m + slot; the row is
+ * committed to the Summary Token Buffer (the paper's commit step).  A sequence whose pos is outside the cache
+ * is skipped.  Errors: INVALID_ARG (null or misaligned pointers, unknown kind, kind = SUMMARY with m = 0), HIP.
+ */
+int ksa_cache_append(const ksa_params *params /*host*/, int32_t kind, const void *k_new, const void *v_new,
+                     const int32_t *pos, void *k_cache, void *v_cache, const int64_t cache_strides[3],
+                     void *stream);
+
+/*
+ * Rows a summary token with ordinal u = j*m + slot reads (Eq. 3, summary rows): the text of its own chunk j
+ * (c ring rows) and the summaries of the same chunk up to itself (only itself with params->flags bit 0).
+ * out = {off0, len0, off1, len1}: summary buffer range, ring range.
+ */
+int ksa_decode_summary_ranges(const ksa_params *params /*host*/, int64_t ordinal, int32_t out[4]);
+
+/*
+ * ksa_decode_summary_fwd: the summary-token step of the decode loop: one summary query per sequence, run when
+ * a chunk has been completed.  Arguments as ksa_decode_fwd, except that ordinal[b] (device int32 [B]) is the
+ * summary ordinal j*m + slot of the query; the K/V rows of the chunk's text and of the summary itself must be in
+ * the cache (ksa_cache_append).  Same kernels as ksa_decode_fwd over at most c + m rows.
+ */
+int ksa_decode_summary_fwd(const ksa_params *params /*host*/, const void *q, const void *k_cache,
+                           const void *v_cache, const int32_t *ordinal, void *o, float *lse,
+                           const int64_t cache_strides[3], void *workspace, size_t workspace_bytes,
+                           int32_t n_splits, void *stream);
+
 const char *ksa_status_string(int status);
 /* Static description of the build: tile sizes and the gfx target, e.g. for logs. */
 const char *ksa_build_info(void);

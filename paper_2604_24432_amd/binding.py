@@ -75,6 +75,10 @@ def lib():
         "ksa_decode_ranges": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_decode_workspace_bytes": (C.c_size_t, [pp, C.c_int32]),
         "ksa_decode_fwd": (C.c_int, [pp, vp, vp, vp, vp, vp, vp, i64p, vp, C.c_size_t, C.c_int32, vp]),
+        "ksa_decode_summary_ranges": (C.c_int, [pp, C.c_int64, i32p]),
+        "ksa_decode_summary_fwd": (C.c_int, [pp, vp, vp, vp, vp, vp, vp, i64p, vp, C.c_size_t, C.c_int32, vp]),
+        "ksa_cache_from_prefill": (C.c_int, [pp, C.c_int64, vp, vp, i64p, vp, vp, i64p, vp]),
+        "ksa_cache_append": (C.c_int, [pp, C.c_int32, vp, vp, vp, vp, vp, i64p, vp]),
         "ksa_status_string": (C.c_char_p, [C.c_int]),
         "ksa_build_info": (C.c_char_p, []),
     }
@@ -89,7 +93,8 @@ EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload
                     "ksa_layout_index_maps", "ksa_layout_row_ranges", "ksa_layout_mask_row",
                     "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v", "ksa_cache_geometry", "ksa_cache_text_row",
                     "ksa_cache_summary_row", "ksa_decode_ranges", "ksa_decode_workspace_bytes",
-                    "ksa_decode_fwd", "ksa_status_string", "ksa_build_info")
+                    "ksa_decode_fwd", "ksa_decode_summary_ranges", "ksa_decode_summary_fwd", "ksa_cache_from_prefill",
+                    "ksa_cache_append", "ksa_status_string", "ksa_build_info")
 
 
 def status_string(status: int) -> str:
@@ -270,9 +275,7 @@ def decode_workspace_bytes(params: ksa_params, n_splits: int = 0) -> int:
     return int(lib().ksa_decode_workspace_bytes(C.byref(params), n_splits))
 
 
-def ksa_decode_fwd(params: ksa_params, q, k_cache, v_cache, pos, o=None, lse=None, return_lse=True,
-                   workspace=None, n_splits: int = 0, stream=None):
-    """q [B, Hq, d] bf16; caches [B, Hkv, cache_rows, d] bf16; pos int32 [B] on the GPU."""
+def _decode(entry, params: ksa_params, q, k_cache, v_cache, pos, o, lse, return_lse, workspace, n_splits, stream):
     import torch
     _require(q, "q", torch.bfloat16, 3)
     _require(k_cache, "k_cache", torch.bfloat16, 4)
@@ -293,13 +296,77 @@ def ksa_decode_fwd(params: ksa_params, q, k_cache, v_cache, pos, o=None, lse=Non
     need = decode_workspace_bytes(params, n_splits)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    rc = lib().ksa_decode_fwd(C.byref(params), C.c_void_p(q.data_ptr()), C.c_void_p(k_cache.data_ptr()),
-                              C.c_void_p(v_cache.data_ptr()), C.c_void_p(pos.data_ptr()), C.c_void_p(o.data_ptr()),
-                              C.c_void_p(lse.data_ptr()) if lse is not None else None,
-                              _strides3(k_cache, (0, 1, 2)), C.c_void_p(workspace.data_ptr()),
-                              workspace.numel() * workspace.element_size(), n_splits, _stream_ptr(stream))
-    _check(rc, "ksa_decode_fwd")
+    rc = getattr(lib(), entry)(C.byref(params), C.c_void_p(q.data_ptr()), C.c_void_p(k_cache.data_ptr()),
+                               C.c_void_p(v_cache.data_ptr()), C.c_void_p(pos.data_ptr()), C.c_void_p(o.data_ptr()),
+                               C.c_void_p(lse.data_ptr()) if lse is not None else None,
+                               _strides3(k_cache, (0, 1, 2)), C.c_void_p(workspace.data_ptr()),
+                               workspace.numel() * workspace.element_size(), n_splits, _stream_ptr(stream))
+    _check(rc, entry)
     return o, lse
+
+
+def ksa_decode_fwd(params: ksa_params, q, k_cache, v_cache, pos, o=None, lse=None, return_lse=True,
+                   workspace=None, n_splits: int = 0, stream=None):
+    """q [B, Hq, d] bf16; caches [B, Hkv, cache_rows, d] bf16; pos int32 [B] on the GPU (text indices)."""
+    return _decode("ksa_decode_fwd", params, q, k_cache, v_cache, pos, o, lse, return_lse, workspace, n_splits, stream)
+
+
+def ksa_decode_summary_fwd(params: ksa_params, q, k_cache, v_cache, ordinal, o=None, lse=None, return_lse=True,
+                           workspace=None, n_splits: int = 0, stream=None):
+    """The summary-token step: as ksa_decode_fwd with ordinal int32 [B] = summary ordinals j*m + slot."""
+    return _decode("ksa_decode_summary_fwd", params, q, k_cache, v_cache, ordinal, o, lse, return_lse, workspace,
+                   n_splits, stream)
+
+
+def ksa_decode_summary_ranges(params: ksa_params, ordinal: int) -> np.ndarray:
+    out = (C.c_int32 * 4)()
+    _check(lib().ksa_decode_summary_ranges(C.byref(params), ordinal, out), "ksa_decode_summary_ranges")
+    return np.array(out[:], np.int32)
+
+
+KSA_ROW_TEXT, KSA_ROW_SUMMARY = 0, 1
+
+
+def _check_cache(params, k_cache, v_cache):
+    import torch
+    _require(k_cache, "k_cache", torch.bfloat16, 4)
+    _require(v_cache, "v_cache", torch.bfloat16, 4)
+    s_cap, rows = cache_geometry(params)
+    if tuple(k_cache.shape) != (params.batch, params.n_kv_heads, rows, params.head_dim) or \
+            k_cache.shape != v_cache.shape or k_cache.stride() != v_cache.stride():
+        raise ValueError(f"cache shape must be {(params.batch, params.n_kv_heads, rows, params.head_dim)}")
+
+
+def ksa_cache_from_prefill(params: ksa_params, n_prefill: int, k, v, k_cache, v_cache, stream=None):
+    """k, v [B, L, Hkv, d] bf16: augmented sequence of n_prefill text tokens; fills the caches in place."""
+    import torch
+    _require(k, "k", torch.bfloat16, 4)
+    _require(v, "v", torch.bfloat16, 4)
+    _check_cache(params, k_cache, v_cache)
+    L = n_prefill // max(params.chunk_len, 1) * (params.chunk_len + params.n_summary)
+    if tuple(k.shape) != (params.batch, L, params.n_kv_heads, params.head_dim) or k.shape != v.shape or \
+            k.stride() != v.stride() or k.stride(3) != 1:
+        raise ValueError(f"k / v shape must be {(params.batch, L, params.n_kv_heads, params.head_dim)}")
+    rc = lib().ksa_cache_from_prefill(C.byref(params), n_prefill, C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
+                                      _strides3(k, (0, 1, 2)), C.c_void_p(k_cache.data_ptr()),
+                                      C.c_void_p(v_cache.data_ptr()), _strides3(k_cache, (0, 1, 2)), _stream_ptr(stream))
+    _check(rc, "ksa_cache_from_prefill")
+
+
+def ksa_cache_append(params: ksa_params, kind: int, k_new, v_new, pos, k_cache, v_cache, stream=None):
+    """k_new, v_new [B, Hkv, d] bf16 contiguous; pos int32 [B] on the GPU (text indices or summary ordinals)."""
+    import torch
+    _require(k_new, "k_new", torch.bfloat16, 3)
+    _require(v_new, "v_new", torch.bfloat16, 3)
+    _require(pos, "pos", torch.int32, 1)
+    _check_cache(params, k_cache, v_cache)
+    if tuple(k_new.shape) != (params.batch, params.n_kv_heads, params.head_dim) or k_new.shape != v_new.shape or \
+            not k_new.is_contiguous() or not v_new.is_contiguous() or pos.shape[0] != params.batch:
+        raise ValueError("k_new / v_new / pos shape does not match params")
+    rc = lib().ksa_cache_append(C.byref(params), kind, C.c_void_p(k_new.data_ptr()), C.c_void_p(v_new.data_ptr()),
+                                C.c_void_p(pos.data_ptr()), C.c_void_p(k_cache.data_ptr()),
+                                C.c_void_p(v_cache.data_ptr()), _strides3(k_cache, (0, 1, 2)), _stream_ptr(stream))
+    _check(rc, "ksa_cache_append")
 
 
 def pack_cache(params: ksa_params, k_sum, v_sum, k_txt, v_txt, txt_base: int):

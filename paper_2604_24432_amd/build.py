@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libksa.so")
-SOURCES = ["ksa_layout.cpp", "ksa_api.cpp", "ksa_prefill.hip", "ksa_decode.hip"]
+SOURCES = ["ksa_layout.cpp", "ksa_api.cpp", "ksa_prefill.hip", "ksa_decode.hip", "ksa_cache.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU instructions are kept out of the generated code (hand-written none either)

@@ -121,9 +121,11 @@ size_t ksa_decode_workspace_bytes(const ksa_params *p, int32_t n_splits) {
     return (size_t)p->batch * p->n_q_heads * n_splits * (p->head_dim + 2) * sizeof(float);
 }
 
-int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
-                   const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
-                   size_t workspace_bytes, int32_t n_splits, void *stream) {
+namespace {
+
+int decode_call(const ksa_params *p, int32_t kind, const void *q, const void *k_cache, const void *v_cache,
+                const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
+                size_t workspace_bytes, int32_t n_splits, void *stream) {
     int32_t s_cap = 0, rows = 0;
     const int rc = ksa_cache_geometry(p, &s_cap, &rows);
     if (rc != KSA_OK) return rc;
@@ -131,6 +133,7 @@ int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, cons
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o) || !aligned16(workspace))
         return KSA_ERR_INVALID_ARG;
     if (n_splits < 0 || n_splits > 1024) return KSA_ERR_INVALID_ARG;
+    if (kind == KSA_ROW_SUMMARY && p->n_summary == 0) return KSA_ERR_INVALID_ARG;
     if (p->n_q_heads / p->n_kv_heads > 8) return KSA_ERR_UNSUPPORTED;
     if (n_splits == 0) n_splits = ksa_decode_default_splits(p);
     if (workspace_bytes < ksa_decode_workspace_bytes(p, n_splits)) return KSA_ERR_WORKSPACE_TOO_SMALL;
@@ -141,9 +144,74 @@ int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, cons
     a.workspace = static_cast<float *>(workspace);
     a.n_splits = n_splits;
     a.summary_capacity = s_cap;
+    a.kind = kind;
     a.p = *p;
     if (a.p.softmax_scale <= 0.f) a.p.softmax_scale = 1.0f / __builtin_sqrtf((float)p->head_dim);
     return ksa_launch_decode(a, stream);
+}
+
+}  // namespace
+
+int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
+                   size_t workspace_bytes, int32_t n_splits, void *stream) {
+    return decode_call(p, KSA_ROW_TEXT, q, k_cache, v_cache, pos, o, lse, cache_strides, workspace, workspace_bytes,
+                       n_splits, stream);
+}
+
+int ksa_decode_summary_fwd(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *ordinal, void *o, float *lse, const int64_t cache_strides[3],
+                           void *workspace, size_t workspace_bytes, int32_t n_splits, void *stream) {
+    return decode_call(p, KSA_ROW_SUMMARY, q, k_cache, v_cache, ordinal, o, lse, cache_strides, workspace,
+                       workspace_bytes, n_splits, stream);
+}
+
+int ksa_cache_from_prefill(const ksa_params *p, int64_t n_prefill, const void *k, const void *v,
+                           const int64_t kv_strides[3], void *k_cache, void *v_cache,
+                           const int64_t cache_strides[3], void *stream) {
+    int32_t s_cap = 0, rows = 0;
+    const int rc = ksa_cache_geometry(p, &s_cap, &rows);
+    if (rc != KSA_OK) return rc;
+    if (n_prefill < 0 || n_prefill % p->chunk_len != 0) return KSA_ERR_INVALID_ARG;
+    if (n_prefill > p->n_text) return KSA_ERR_OUT_OF_RANGE;
+    if (!k_cache || !v_cache || !aligned16(k_cache) || !aligned16(v_cache)) return KSA_ERR_INVALID_ARG;
+    if (n_prefill == 0) return KSA_OK;   // nothing to hand over (k and v may be NULL then)
+    if (!k || !v || !aligned16(k) || !aligned16(v)) return KSA_ERR_INVALID_ARG;
+    KsaCacheFillLaunch a;
+    const int64_t L = n_prefill / p->chunk_len * (int64_t)(p->chunk_len + p->n_summary);
+    if (kv_strides) {
+        for (int x = 0; x < 3; ++x) a.kv_strides[x] = kv_strides[x];
+    } else {   // contiguous [B, L, Hkv, d]: {batch, row, head}
+        a.kv_strides[2] = p->head_dim;
+        a.kv_strides[1] = (int64_t)p->n_kv_heads * p->head_dim;
+        a.kv_strides[0] = L * a.kv_strides[1];
+    }
+    default_strides(a.cache_strides, cache_strides, p->n_kv_heads, rows, p->head_dim);
+    if (!strides_ok(a.kv_strides) || !strides_ok(a.cache_strides)) return KSA_ERR_INVALID_ARG;
+    a.k = k, a.v = v, a.k_cache = k_cache, a.v_cache = v_cache;
+    a.n_prefill = n_prefill;
+    a.summary_capacity = s_cap;
+    a.p = *p;
+    return ksa_launch_cache_fill(a, stream);
+}
+
+int ksa_cache_append(const ksa_params *p, int32_t kind, const void *k_new, const void *v_new, const int32_t *pos,
+                     void *k_cache, void *v_cache, const int64_t cache_strides[3], void *stream) {
+    int32_t s_cap = 0, rows = 0;
+    const int rc = ksa_cache_geometry(p, &s_cap, &rows);
+    if (rc != KSA_OK) return rc;
+    if (kind != KSA_ROW_TEXT && kind != KSA_ROW_SUMMARY) return KSA_ERR_INVALID_ARG;
+    if (kind == KSA_ROW_SUMMARY && p->n_summary == 0) return KSA_ERR_INVALID_ARG;
+    if (!k_new || !v_new || !pos || !k_cache || !v_cache) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return KSA_ERR_INVALID_ARG;
+    KsaCacheAppendLaunch a;
+    default_strides(a.cache_strides, cache_strides, p->n_kv_heads, rows, p->head_dim);
+    if (!strides_ok(a.cache_strides)) return KSA_ERR_INVALID_ARG;
+    a.k_new = k_new, a.v_new = v_new, a.pos = pos, a.k_cache = k_cache, a.v_cache = v_cache;
+    a.kind = kind;
+    a.summary_capacity = s_cap;
+    a.p = *p;
+    return ksa_launch_cache_append(a, stream);
 }
 
 const char *ksa_build_info(void) {

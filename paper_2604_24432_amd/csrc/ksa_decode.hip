@@ -28,19 +28,36 @@ struct DecodeArgs {
     float *ws;
     int64_t cs[3];   // {batch, head, row} strides of the caches in elements
     int32_t n_splits, s_cap;
+    int32_t kind, self_only;   // KSA_ROW_TEXT / KSA_ROW_SUMMARY query; flag bit 0 of the parameters
     int32_t c, m, C, n_text;
     int32_t n_q_heads, n_kv_heads;
     float scale_log2e;
 };
 
 struct Ranges {
-    int n0, off1, n1, off2, n2;   // summaries [0,n0), ring [off1, off1+n1), ring [off2, off2+n2)
+    int off0, n0, off1, n1, off2, n2;   // summaries [off0, off0+n0), ring [off1, off1+n1), ring [off2, off2+n2)
 };
 
-// Rows a token at text index p reads (Eq. 3 mapped onto the cache geometry); all zero if p is invalid.
+// Is p a position the query kind can have?  (text index / summary ordinal)
+__device__ __forceinline__ bool valid_pos(const DecodeArgs &a, int p) {
+    return p >= 0 && p < (a.kind == KSA_ROW_TEXT ? a.n_text : a.s_cap);
+}
+
+// Rows the query reads (Eq. 3 mapped onto the cache geometry); all zero if p is invalid.
+// Text token at text index p: the summaries of the chunks that have left the window and the text of the window up to
+// itself.  Summary token with ordinal p = j m + slot: the summaries of its chunk up to itself (only itself with
+// self_only) and the text of its chunk, one whole ring slot.
 __device__ __forceinline__ Ranges visible_rows(const DecodeArgs &a, int p) {
-    Ranges R = {0, 0, 0, 0, 0};
-    if (p < 0 || p >= a.n_text) return R;
+    Ranges R = {0, 0, 0, 0, 0, 0};
+    if (!valid_pos(a, p)) return R;
+    if (a.kind == KSA_ROW_SUMMARY) {
+        const int j = p / a.m, slot = p - j * a.m;
+        R.off0 = a.self_only ? p : j * a.m;
+        R.n0 = a.self_only ? 1 : slot + 1;
+        R.off1 = a.s_cap + (j % (a.C + 1)) * a.c;
+        R.n1 = a.c;
+        return R;
+    }
     const int j = p / a.c, r = p - j * a.c;
     const int slot = j % (a.C + 1);
     R.n0 = (j - a.C > 0 ? j - a.C : 0) * a.m;
@@ -52,7 +69,7 @@ __device__ __forceinline__ Ranges visible_rows(const DecodeArgs &a, int p) {
 }
 
 __device__ __forceinline__ int phys_row(const Ranges &R, int v) {
-    if (v < R.n0) return v;
+    if (v < R.n0) return R.off0 + v;
     v -= R.n0;
     if (v < R.n1) return R.off1 + v;
     return R.off2 + (v - R.n1);
@@ -209,8 +226,7 @@ template <int D>
 __global__ __launch_bounds__(D) void ksa_decode_merge_kernel(const DecodeArgs a) {
     const int hq = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
     const float *rec = a.ws + ((int64_t)b * a.n_q_heads + hq) * a.n_splits * (D + 2);
-    const int p = a.pos[b];
-    const bool valid = p >= 0 && p < a.n_text;
+    const bool valid = valid_pos(a, a.pos[b]);
     float M = -1e30f;
     for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, rec[s * (D + 2) + D]);
     float acc = 0.f, den = 0.f;
@@ -270,6 +286,8 @@ int ksa_launch_decode(const KsaDecodeLaunch &L, void *stream) {
     for (int x = 0; x < 3; ++x) a.cs[x] = L.cache_strides[x];
     a.n_splits = L.n_splits;
     a.s_cap = L.summary_capacity;
+    a.kind = L.kind;
+    a.self_only = (L.p.flags & 1u) ? 1 : 0;
     a.c = L.p.chunk_len;
     a.m = L.p.n_summary;
     a.C = L.p.window_chunks;

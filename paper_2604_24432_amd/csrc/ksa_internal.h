@@ -51,9 +51,31 @@ struct KsaDecodeLaunch {
     float *workspace;
     int32_t n_splits;
     int32_t summary_capacity;
+    int32_t kind;             // KSA_ROW_TEXT: pos is a text index; KSA_ROW_SUMMARY: pos is a summary ordinal
     ksa_params p;
 };
 int ksa_launch_decode(const KsaDecodeLaunch &a, void *stream);
+
+struct KsaCacheFillLaunch {
+    const void *k, *v;
+    void *k_cache, *v_cache;
+    int64_t kv_strides[3], cache_strides[3];
+    int64_t n_prefill;
+    int32_t summary_capacity;
+    ksa_params p;
+};
+int ksa_launch_cache_fill(const KsaCacheFillLaunch &a, void *stream);
+
+struct KsaCacheAppendLaunch {
+    const void *k_new, *v_new;
+    const int32_t *pos;
+    void *k_cache, *v_cache;
+    int64_t cache_strides[3];
+    int32_t kind;
+    int32_t summary_capacity;
+    ksa_params p;
+};
+int ksa_launch_cache_append(const KsaCacheAppendLaunch &a, void *stream);
 int ksa_decode_default_splits(const ksa_params *p);
 
 #endif

@@ -315,6 +315,25 @@ int ksa_cache_summary_row(const ksa_params *p, int64_t u, int32_t *row) {
     return KSA_OK;
 }
 
+int ksa_decode_summary_ranges(const ksa_params *p, int64_t u, int32_t out[4]) {
+    int32_t s_cap;
+    const int rc = ksa_cache_geometry(p, &s_cap, nullptr);
+    if (rc != KSA_OK) return rc;
+    if (!out) return KSA_ERR_INVALID_ARG;
+    if (p->n_summary == 0) return KSA_ERR_INVALID_ARG;
+    if (u < 0 || u >= s_cap) return KSA_ERR_OUT_OF_RANGE;
+    const int64_t c = p->chunk_len, C = p->window_chunks, m = p->n_summary;
+    const int64_t j = u / m, slot = u % m;
+    // summaries of the same chunk up to and including itself (Eq. 3, summary rows); only itself with flag bit 0
+    const bool self_only = (p->flags & 1u) != 0;
+    out[0] = (int32_t)(self_only ? u : j * m);
+    out[1] = (int32_t)(self_only ? 1 : slot + 1);
+    // the text of its own chunk: one whole ring slot
+    out[2] = (int32_t)(s_cap + (j % (C + 1)) * c);
+    out[3] = (int32_t)c;
+    return KSA_OK;
+}
+
 int ksa_decode_ranges(const ksa_params *p, int64_t pos, int32_t out[6]) {
     int32_t s_cap;
     const int rc = ksa_cache_geometry(p, &s_cap, nullptr);
