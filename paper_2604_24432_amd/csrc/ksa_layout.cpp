@@ -61,13 +61,17 @@ KsaWorkItem text_item(const ksa_params &p, int64_t t0, int32_t cnt) {
         push_segment(it, KSA_SPACE_SUMMARY, 0, full_end, 0);
         push_segment(it, KSA_SPACE_SUMMARY, full_end, seen_by_any, 1);
     }
-    // sliding-chunk text: [lo_first, ...) is seen by the first row's chunk, [lo_last, t0] by every row
+    // sliding-chunk text: [lo_first, ...) is seen by the first row's chunk, [lo_last, t0] by every row.  The run that
+    // every row sees whole starts at the next multiple of the key tile, so that all three runs start on the tile grid
+    // of the index space whenever lo_first does (the kernel's pipelined loop wants run starts that are multiples of
+    // 16); the keys between lo_last and that boundary stay in the masked run in front of it.
     const int64_t lo_first = pos_part(j0 - C) * c, lo_last = pos_part(j1 - C) * c;
-    const int64_t full_tiles = lo_last < t0 ? (t0 - lo_last) / KSA_K_TILE : 0;
+    const int64_t full_begin = (lo_last + KSA_K_TILE - 1) / KSA_K_TILE * KSA_K_TILE;
+    const int64_t full_tiles = full_begin < t0 ? (t0 - full_begin) / KSA_K_TILE : 0;
     if (full_tiles > 0) {
-        push_segment(it, KSA_SPACE_TEXT, lo_first, lo_last, 1);
-        push_segment(it, KSA_SPACE_TEXT, lo_last, lo_last + full_tiles * KSA_K_TILE, 0);
-        push_segment(it, KSA_SPACE_TEXT, lo_last + full_tiles * KSA_K_TILE, t0 + cnt, 1);
+        push_segment(it, KSA_SPACE_TEXT, lo_first, full_begin, 1);
+        push_segment(it, KSA_SPACE_TEXT, full_begin, full_begin + full_tiles * KSA_K_TILE, 0);
+        push_segment(it, KSA_SPACE_TEXT, full_begin + full_tiles * KSA_K_TILE, t0 + cnt, 1);
     } else {
         push_segment(it, KSA_SPACE_TEXT, lo_first, t0 + cnt, 1);
     }

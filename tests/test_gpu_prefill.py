@@ -108,6 +108,8 @@ SMALL = [
     ("window0", 1, 4, 4, 128, 512, 64, 8, 0),
     ("window3", 1, 2, 1, 128, 1024, 64, 8, 3),
     ("paper_m1_c8", 1, 4, 2, 128, 1024, 8, 1, 16),        # the paper's own form: one summary per chunk of 8
+    ("paper_m1_c8_C128", 1, 2, 1, 128, 2560, 8, 1, 128),  # ... with its window of 128 chunks (runs start off the chunk grid)
+    ("sliding_window", 1, 2, 2, 128, 1536, 64, 0, 5),     # no summaries, window of 5 chunks
     ("odd_chunk", 1, 2, 2, 64, 600, 20, 5, 1),            # chunk length not a power of two
     ("no_summaries_sca", 1, 2, 1, 128, 640, 32, 0, 2),    # Eq. 2 alone
     ("dense_causal", 1, 2, 2, 64, 320, 320, 0, 0),        # single chunk, no summaries
