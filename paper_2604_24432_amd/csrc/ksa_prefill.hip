@@ -4,20 +4,21 @@
 // each wave owns 32*QB query rows.  Scores are produced TRANSPOSED, S^T = K Q^T, with
 // v_mfma_f32_32x32x16_bf16: the 32x32 result block gives lane l the query column l%32 and the key rows
 // 8*(g/4) + 4*(l/32) + g%4 for its 16 registers g, so
-//   - the softmax statistics of a query row live in one lane pair (l, l^32): row max and row sum are
-//     in-lane reductions plus one v_permlane32_swap, no LDS, no shuffle tree;
+//   - the softmax statistics of a query row live in one lane pair (l, l^32): the row maximum is an in-lane
+//     reduction plus one v_permlane32_swap, no LDS, no shuffle tree;
 //   - the same registers, rounded to bf16, are already the B operand of O^T += V^T P^T (eight registers
 //     of one lane = eight k slots), so P never leaves the register file;
 //   - the rescale factor of the output accumulator is a per-lane scalar.
-// K and V tiles (64 keys) go from global memory straight into LDS (global_load_lds_dwordx4, no VGPR
-// staging) with an XOR swizzle of the 16-byte chunks applied on the global side; the K operand is read
-// with ds_read_b128, the V^T operand with the gfx950 transposing read ds_read_b64_tr_b16, which hands each
-// lane four consecutive keys of one head-dim column out of the row-major [key][d] tile.
+// K tiles (64 keys) go from global memory straight into LDS (global_load_lds_dwordx4, no VGPR staging) with
+// an XOR swizzle of the 16-byte chunks applied on the global side and are read with ds_read_b128.
 //
-// Two loops share the accumulators.  Runs of FULL tiles (no mask; almost all of the work at long context:
-// text rows against distant summaries) take a software-pipelined loop with double-buffered LDS in which the
-// score MFMAs of tile t+1 are issued next to the softmax arithmetic of tile t.  MASKED runs (window edges,
-// the causal diagonal, summary rows) take a plain loop that clips every query row to its visible range.
+// Two kernels come out of one template.  PIPELINED = true (work items all of whose key runs meet the
+// conditions the scheduler checks; every item of the paper's shapes): a software-pipelined loop over 32-key
+// sub-tiles, three LDS buffers per operand, V read from a key-major copy made by ksa_vt_kernel so that the
+// V^T operand is one ds_read_b128 as well; masked runs (window edges, the causal diagonal, summary rows) go
+// through the same loop and clip every score to its row's visible key range.  PIPELINED = false: the
+// remaining items, with a plain load -> compute loop per tile and the gfx950 transposing LDS read
+// (ds_read_b64_tr_b16) for V^T out of the row-major tile.
 // The running maximum is only raised when a tile exceeds it by more than 2^8 in the exponent domain, so the
 // accumulator rescale almost never runs; results are unchanged because the final 1/l normalisation uses
 // the same reference.
@@ -25,8 +26,8 @@
 // Rows are addressed in two compact index spaces, text index i and summary ordinal u (Eq. 1):
 //   augmented row of text i    = (i / c) * (c + m) + i % c
 //   augmented row of summary u = (u / m) * (c + m) + c + u % m
-// and every query row's visible set is one range of each space (Eq. 3), so a masked tile costs two
-// integer compares per score.
+// and every query row's visible set is one range of each space (Eq. 3), so a masked score costs one add,
+// one unsigned compare and one select.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -38,14 +39,12 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
-#define GLOBAL_PTR(T) __attribute__((address_space(1))) T *
 
 #ifndef KSA_PIN
 #define KSA_PIN 1
@@ -420,14 +419,6 @@ __device__ __forceinline__ void exp_and_pack(const f32x16 (&sacc)[QB][2], bf16x8
 template <int D>
 __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char *lds, int lk, int s) {
     return *reinterpret_cast<const bf16x8 *>(lds + (lk ^ (s << 5)));
-}
-
-template <int D>
-__device__ __forceinline__ bf16x8 read_v_operand(const unsigned char *lds, int lv, int hf, int db) {
-    const int a0 = (lv ^ (db << 6)) + hf * 16 * (D * 2), a1 = a0 + 8 * (D * 2);
-    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a0));
-    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + a1));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 // V^T operand (32 head-dim rows x 16 keys) out of a key-major tile: one 16-byte read per lane
