@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-full-attention", action="store_true",
+                    help="skip the dense-causal reference run at the same length (about half a second of GPU time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-splits", type=int, default=0)
     ap.add_argument("--traffic-probe", action="store_true",
@@ -183,9 +185,34 @@ def main():
     }
 
     out["cache_lifecycle"] = cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args)
+    if not args.no_full_attention:
+        del k_cache, v_cache
+        out["full_attention_reference"] = full_attention_reference(cfg, q, k, v, pre_avg)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
     print(json.dumps(out), flush=True)
+
+
+def full_attention_reference(cfg, q, k, v, ksa_ms):
+    """Not part of the timed step: dense causal attention over the same number of text tokens through the same
+    library (no summaries, every earlier chunk in the window), i.e. what the summary mask saves at this length."""
+    import torch
+    import paper_2604_24432_amd as K
+    n, c = cfg.n_text, cfg.chunk_len
+    p = K.make_params(cfg.batch, n, c, 0, n // c, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    lay = K.ksa_build_layout(p)
+    lay.upload()
+    qd, kd, vd = q[:, :n], k[:, :n], v[:, :n]     # the first n rows of the synthetic tensors serve as the text tokens
+    od = torch.empty_like(qd)
+    ld = torch.empty((cfg.batch, cfg.n_q_heads, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty(K.prefill_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+    K.ksa_prefill_fwd(lay, qd, kd, vd, o=od, lse=ld, workspace=ws)
+    ms = float(np.mean(time_events(lambda: K.ksa_prefill_fwd(lay, qd, kd, vd, o=od, lse=ld, workspace=ws), 3)))
+    flops = 4.0 * cfg.head_dim * cfg.batch * cfg.n_q_heads * live_pairs(n, c, 0, n // c)
+    return {"workload": f"dense causal, B{cfg.batch} Hq{cfg.n_q_heads} Hkv{cfg.n_kv_heads} d{cfg.head_dim} n{n}",
+            "ms": round(ms, 3), "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "ksa_prefill_speedup": round(ms / ksa_ms, 2)}
 
 
 def cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args):

@@ -166,6 +166,23 @@ def test_prefill_32k_sampled_rows_with_outlier_keys():
     sampled_compare(synth.CONFIGS["prefill_32k"], n_random=384)
 
 
+MEDIUM = [
+    # name, B, Hq, Hkv, d, n, c, m, C, outlier fraction: long runs through the pipelined loop at other shapes than the
+    # benchmark's (head_dim 64, the paper's own chunk form, a sliding window without summaries, batch > 1)
+    ("d64_8k", 2, 4, 2, 64, 8192, 64, 8, 1, 0.0),
+    ("paper_form_8k", 1, 4, 4, 128, 8192, 8, 1, 128, 0.01),
+    ("sliding_8k", 1, 2, 1, 128, 8192, 64, 0, 7, 0.0),
+    ("dense_4k", 1, 2, 2, 128, 4096, 4096, 0, 0, 0.01),
+]
+
+
+@pytest.mark.parametrize("case", MEDIUM, ids=[s[0] for s in MEDIUM])
+def test_medium_shapes_sampled_rows(case):
+    name, B, Hq, Hkv, d, n, c, m, C, frac = case
+    cfg = synth.KsaConfig(name, B, Hq, Hkv, d, n, c, m, C, seed=900 + len(name), key_outlier_frac=frac)
+    sampled_compare(cfg, n_random=256)
+
+
 def test_prefill_128k_sampled_rows():
     sampled_compare(synth.CONFIGS["prefill_128k"], n_random=160)
 
