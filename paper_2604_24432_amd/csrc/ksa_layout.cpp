@@ -35,14 +35,22 @@ inline void summary_row_ranges(const ksa_params &p, int64_t u, int32_t out[4]) {
 
 inline int32_t tiles_in(const KsaSegment &s) { return (s.end - s.begin + KSA_K_TILE - 1) / KSA_K_TILE; }
 
-void push_segment(KsaWorkItem &it, int32_t space, int64_t begin, int64_t end, int32_t masked) {
+void push_segment(KsaWorkItem &it, int32_t space, int64_t begin, int64_t end, int64_t full_lo, int64_t full_hi) {
     if (end <= begin) return;
     KsaSegment &s = it.seg[it.n_seg++];
     s.space = space;
     s.begin = (int32_t)begin;
     s.end = (int32_t)end;
-    s.masked = masked;
+    s.full_lo = (int32_t)full_lo;
+    s.full_hi = (int32_t)full_hi;
+    s.pad = 0;
     it.n_tiles += tiles_in(s);
+}
+
+// Does tile t of the run need no mask?
+inline bool tile_is_full(const KsaSegment &s, int32_t t) {
+    const int64_t k0 = (int64_t)s.begin + (int64_t)t * KSA_K_TILE;
+    return k0 >= s.full_lo && k0 + KSA_K_TILE <= s.full_hi;
 }
 
 // Query tile of text rows [t0, t0+cnt).
@@ -54,27 +62,11 @@ KsaWorkItem text_item(const ksa_params &p, int64_t t0, int32_t cnt) {
     it.q_count = cnt;
     const int64_t c = p.chunk_len, m = p.n_summary, C = p.window_chunks;
     const int64_t j0 = t0 / c, j1 = (t0 + cnt - 1) / c;
-    // distant summaries: the first row's chunk sees the fewest, the last row's chunk the most
-    if (m > 0) {
-        const int64_t seen_by_all = pos_part(j0 - C) * m, seen_by_any = pos_part(j1 - C) * m;
-        const int64_t full_end = seen_by_all / KSA_K_TILE * KSA_K_TILE;
-        push_segment(it, KSA_SPACE_SUMMARY, 0, full_end, 0);
-        push_segment(it, KSA_SPACE_SUMMARY, full_end, seen_by_any, 1);
-    }
-    // sliding-chunk text: [lo_first, ...) is seen by the first row's chunk, [lo_last, t0] by every row.  The run that
-    // every row sees whole starts at the next multiple of the key tile, so that all three runs start on the tile grid
-    // of the index space whenever lo_first does (the kernel's pipelined loop wants run starts that are multiples of
-    // 16); the keys between lo_last and that boundary stay in the masked run in front of it.
+    // distant summaries: the first row's chunk sees the fewest (those every row sees), the last row's chunk the most
+    if (m > 0) push_segment(it, KSA_SPACE_SUMMARY, 0, pos_part(j1 - C) * m, 0, pos_part(j0 - C) * m);
+    // sliding-chunk text: [lo_first, ...) is seen by the first row's chunk, [lo_last, t0) by every row
     const int64_t lo_first = pos_part(j0 - C) * c, lo_last = pos_part(j1 - C) * c;
-    const int64_t full_begin = (lo_last + KSA_K_TILE - 1) / KSA_K_TILE * KSA_K_TILE;
-    const int64_t full_tiles = full_begin < t0 ? (t0 - full_begin) / KSA_K_TILE : 0;
-    if (full_tiles > 0) {
-        push_segment(it, KSA_SPACE_TEXT, lo_first, full_begin, 1);
-        push_segment(it, KSA_SPACE_TEXT, full_begin, full_begin + full_tiles * KSA_K_TILE, 0);
-        push_segment(it, KSA_SPACE_TEXT, full_begin + full_tiles * KSA_K_TILE, t0 + cnt, 1);
-    } else {
-        push_segment(it, KSA_SPACE_TEXT, lo_first, t0 + cnt, 1);
-    }
+    push_segment(it, KSA_SPACE_TEXT, lo_first, t0 + cnt, lo_last, t0);
     return it;
 }
 
@@ -87,8 +79,8 @@ KsaWorkItem summary_item(const ksa_params &p, int64_t u0, int32_t cnt) {
     it.q_count = cnt;
     const int64_t c = p.chunk_len, m = p.n_summary;
     const int64_t j0 = u0 / m, j1 = (u0 + cnt - 1) / m;
-    push_segment(it, KSA_SPACE_TEXT, j0 * c, (j1 + 1) * c, 1);
-    push_segment(it, KSA_SPACE_SUMMARY, j0 * m, u0 + cnt, 1);
+    push_segment(it, KSA_SPACE_TEXT, j0 * c, (j1 + 1) * c, 0, 0);
+    push_segment(it, KSA_SPACE_SUMMARY, j0 * m, u0 + cnt, 0, 0);
     return it;
 }
 
@@ -265,7 +257,7 @@ int ksa_layout_tile_pairs(const ksa_layout *lay, int64_t *n_pairs, uint8_t *q_sp
                 if (k_space) k_space[x] = (uint8_t)it.seg[s].space;
                 if (k_begin) k_begin[x] = kb;
                 if (k_count) k_count[x] = std::min(KSA_K_TILE, it.seg[s].end - kb);
-                if (kind) kind[x] = it.seg[s].masked ? KSA_TILE_MASKED : KSA_TILE_FULL;
+                if (kind) kind[x] = tile_is_full(it.seg[s], (kb - it.seg[s].begin) / KSA_K_TILE) ? KSA_TILE_FULL : KSA_TILE_MASKED;
             }
     *n_pairs = x;
     return KSA_OK;

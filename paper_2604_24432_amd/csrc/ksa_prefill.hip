@@ -328,6 +328,15 @@ __device__ __forceinline__ void raise_reference_pl(RowState &st, const float (&m
                                                    float sl) {
     using T = Tile<D>;
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results reach the register file
+    // The accumulators are re-defined here as far as the compiler can tell: the per-register copies it makes for the
+    // statements below then depend on this block and cannot be hoisted in front of the branch that guards it (where
+    // they would run on every tile).
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        asm volatile("" : "+a"(st.l_sum[qb]));
+#pragma unroll
+        for (int db = 0; db < T::DB; ++db) asm volatile("" : "+a"(oacc[qb][db]));
+    }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float m_new = fmaxf(st.m_ref[qb], fmaxf(mx[qb], other_half(mx[qb])));
@@ -816,7 +825,9 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         const unsigned long long TS0 = KSA_NOW();
 #endif
         const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
-        const bool masked = item.seg[seg].masked != 0;
+        // tiles inside [full_lo, full_hi) are seen whole by every row of the query tile; the others are masked
+        const int full_lo = item.seg[seg].full_lo, full_hi = item.seg[seg].full_hi;
+        auto tile_masked = [&](int key0) { return !(key0 >= full_lo && key0 + BN <= full_hi); };
         const int n_tiles = (seg_end - seg_begin + BN - 1) / BN;
         // Are the lanes' row offsets the same for every tile of the run?  Yes when every tile starts at the same
         // phase of the chunk pattern (64 % period == 0), or never crosses a chunk (period % 64 == 0, aligned).
@@ -865,8 +876,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 vis_lo[qb] = lo - 4 * h;
                 vis_span[qb] = max(hi - lo, 0);
             }
-            auto run = [&](auto masked_tag) {
-                constexpr bool MASKED = decltype(masked_tag)::value;
+            // A run is up to three stretches of tiles: masked ones (a window edge), FULL ones, masked ones (the causal
+            // diagonal, the summary edge).  The pipeline is filled once per run; a stretch is a loop over "produce the
+            // scores of tile tn" = the second sub-tile of tile tn - 1 (scores of the first half of tile tn) followed by the
+            // first sub-tile of tile tn (scores of its second half), instantiated with or without the clipping of those
+            // scores.  (One loop with the choice made per tile costs register copies at every join of the two variants.)
+            {
                 const int second = n_tiles > 1 ? 1 : 0;
                 __syncthreads();                     // earlier readers of the LDS buffers are done
                 issue_tile(0, 0);
@@ -879,9 +894,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 qk_only<D>(lds, K0, ll, qreg, sv_a);
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) scores_ready(sv_a[qb]);
+                const bool first_masked = tile_masked(seg_begin);
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
-                    if (MASKED) {
+                    if (first_masked) {
 #pragma unroll
                         for (int g = 0; g < 16; ++g) {
                             const unsigned rel = (unsigned)(seg_begin - vis_lo[qb] + (8 * (g / 4) + g % 4));
@@ -898,60 +914,78 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 bf16x8 ka_pre[T::RING];
 #pragma unroll
                 for (int s = 0; s < T::RING; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
-                int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles t, t+1, t+2
+                int b_cur = 0, b_nxt = T::BYTES, b_ld = 2 * T::BYTES;   // buffer offsets of tiles tn, tn+1, tn+2
                 TileSync<D> sync;
                 sync.k_off = k_offb;
                 sync.v_off = v_offb;
+                sync.kg = kbase, sync.vg = vtbase, sync.k_dst = k_wave, sync.v_dst = v_wave;
 #ifdef KSA_TRACE
                 const unsigned long long TL0 = KSA_NOW();
                 tr.acc[12] += TL0 - TS0;
 #endif
-                for (int t = 0; t < n_tiles; ++t) {
-                    // The tile loads bypass the compiler's bookkeeping but share the hardware counter with everything
-                    // it loads itself (register reloads from scratch around this loop).  An explicit vmcnt(0) here,
-                    // where only the loads of tile t+1 are in flight and are about to be needed anyway, keeps it from
-                    // placing its own wait further down, behind the requests for tile t+2.
-                    __builtin_amdgcn_s_waitcnt(0x0F70);
-                    // the tile after next; past the end of the run the last tile is requested again (into a free buffer)
-                    const int t_ld = t + 2 < n_tiles ? t + 2 : n_tiles - 1;
-                    sync.kg = kbase + tile_base(t_ld);
-                    sync.vg = vtbase + t_ld * BN;
-                    sync.k_dst = k_wave + b_ld;
-                    sync.v_dst = v_wave + b_ld;
-                    const int key0 = seg_begin + t * BN;
-                    // ---- sub-tile 2t: weights from sv_a, next scores (second half of tile t) into sv_b ----
-                    if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                    raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur, 0,
-                                                     K0 + b_nxt, oacc, st, ind, sl, raise_margin, mxl, sync, key0 + 32, vis_lo,
-                                                     vis_span KSA_TRACE_PASS);
-                    // ---- sub-tile 2t+1: weights from sv_b, next scores (first half of tile t+1) into sv_a ----
-                    // (for the last tile those scores come from a buffer that holds no new tile and are never used)
-                    if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                    raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur, 1,
-                                                      K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl, sync, key0 + BN,
-                                                      vis_lo, vis_span KSA_TRACE_PASS) &&
-                            (t + 1 < n_tiles);
-                    const int b_old = b_cur;
-                    b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
-                }
+                auto stretch = [&](auto masked_tag, int tn_begin, int tn_end) {
+                    constexpr bool MASKED = decltype(masked_tag)::value;
+#ifdef KSA_TRACE
+                    const unsigned long long TT0 = KSA_NOW();
+#endif
+                    for (int tn = tn_begin; tn < tn_end; ++tn) {
+                        const int key0 = seg_begin + tn * BN;
+                        if (tn > 0) {
+                            // ---- second sub-tile of tile tn-1: weights from sv_b, scores of the first half of tile tn into
+                            // sv_a (for tn = n_tiles they come from a buffer that holds no new tile and are never used)
+                            if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                            raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur, 1,
+                                                              K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl, sync,
+                                                              key0, vis_lo, vis_span KSA_TRACE_PASS) &&
+                                    (tn < n_tiles);
+                            const int b_old = b_cur;
+                            b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
+                        }
+                        if (tn < n_tiles) {
+                            // The tile loads bypass the compiler's bookkeeping but share the hardware counter with
+                            // everything it loads itself (register reloads from scratch around this loop).  An explicit
+                            // vmcnt(0) here, where only the loads of tile tn+1 are in flight and are about to be needed
+                            // anyway, keeps it from placing its own wait further down, behind the requests for tile tn+2.
+                            __builtin_amdgcn_s_waitcnt(0x0F70);
+                            // the tile after next; past the end of the run the last tile is requested again (into a free
+                            // buffer)
+                            const int t_ld = tn + 2 < n_tiles ? tn + 2 : n_tiles - 1;
+                            sync.kg = kbase + tile_base(t_ld);
+                            sync.vg = vtbase + t_ld * BN;
+                            sync.k_dst = k_wave + b_ld;
+                            sync.v_dst = v_wave + b_ld;
+                            // ---- first sub-tile of tile tn: weights from sv_a, scores of its second half into sv_b ----
+                            if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                            raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur,
+                                                             0, K0 + b_nxt, oacc, st, ind, sl, raise_margin, mxl, sync,
+                                                             key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
+                        }
+                    }
+#ifdef KSA_TRACE
+                    tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TT0;
+                    tr.acc[MASKED ? 15 : 6] += tn_end - tn_begin;
+#endif
+                };
+                // tiles [f_lo, f_hi) of the run are FULL
+                int f_lo = full_lo > seg_begin ? (full_lo - seg_begin + BN - 1) / BN : 0;
+                int f_hi = full_hi > seg_begin ? (full_hi - seg_begin) / BN : 0;
+                f_hi = min(f_hi, n_tiles);
+                if (f_hi <= f_lo) f_lo = f_hi = 0;
+                // index n_tiles (the last second sub-tile alone) goes with the last stretch
+                if (f_lo > 0) stretch(std::true_type{}, 0, f_lo);
+                if (f_hi > f_lo) stretch(std::false_type{}, f_lo, f_hi < n_tiles ? f_hi : n_tiles + 1);
+                if (f_hi < n_tiles) stretch(std::true_type{}, f_hi, n_tiles + 1);
                 // the request repeated for the last tile is still in flight: let it land before anyone reuses LDS
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 accumulators_settle<D>(oacc, st);
-#ifdef KSA_TRACE
-                tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TL0;
-                tr.acc[MASKED ? 15 : 6] += n_tiles;
-#endif
-            };
-            if (masked)
-                run(std::true_type{});
-            else
-                run(std::false_type{});
+            }
         } else {
         // ================= plain loop: MASKED runs, short runs, odd chunk shapes ============================
         const int wlo = space == KSA_SPACE_TEXT ? wlo_t : wlo_s, whi = space == KSA_SPACE_TEXT ? whi_t : whi_s;
         for (int kt = seg_begin; kt < seg_end; kt += BN) {
             const int t_lo = kt, t_hi = min(kt + BN, seg_end);
             // the wave has nothing visible in this tile (block-diagonal summary rows, window edges): skip the math
+            const bool masked = tile_masked(kt);
             const bool active = !masked || (t_lo < whi && t_hi > wlo);
             const bool ragged = kt + BN > seg_end;
             const int base_aug = aug_row(a, space, kt);

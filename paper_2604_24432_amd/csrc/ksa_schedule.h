@@ -10,17 +10,20 @@
 #define KSA_Q_TILE 256
 #endif
 #define KSA_K_TILE 64
-#define KSA_MAX_SEGMENTS 5
+#define KSA_MAX_SEGMENTS 2
 #define KSA_NUM_XCD 8
 
 // A run of consecutive key rows of one index space, walked in steps of KSA_K_TILE from `begin`.
-// masked == 0: every row of the query tile sees every key of the run (its length is a multiple of
-// KSA_K_TILE); masked == 1: the kernel clips each query row's visible range to [begin, end).
+// Every row of the query tile sees every key in [full_lo, full_hi) (an empty range if full_hi <= full_lo): a key
+// tile that lies inside it needs no mask (FULL); for every other tile of the run the kernel clips each query
+// row's visible range to [begin, end) (MASKED).
 struct KsaSegment {
     int32_t space;   // KSA_SPACE_TEXT / KSA_SPACE_SUMMARY
     int32_t begin;
     int32_t end;
-    int32_t masked;
+    int32_t full_lo;
+    int32_t full_hi;
+    int32_t pad;
 };
 
 // One query tile and the key runs that hold all of its visible keys.
