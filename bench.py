@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="skip everything outside the timed step (cache lifecycle timings, dense reference, CPU baseline): "
+                         "for profiler runs, whose per-kernel statistics then cover the benchmark launches only")
     ap.add_argument("--no-full-attention", action="store_true",
                     help="skip the dense-causal reference run at the same length (about half a second of GPU time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,6 +187,9 @@ def main():
                             "traffic": measured_traffic("decode")},
     }
 
+    if args.hot_path_only:
+        print(json.dumps(out), flush=True)
+        return
     out["cache_lifecycle"] = cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args)
     if not args.no_full_attention:
         del k_cache, v_cache
