@@ -35,7 +35,7 @@ extern "C" {
 
 typedef enum ksa_status {
     KSA_OK = 0,
-    KSA_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, n_text % chunk_len != 0, ... */
+    KSA_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, inconsistent parameters, ... */
     KSA_ERR_UNSUPPORTED = -2,        /* head_dim / group size the kernels were not built for        */
     KSA_ERR_WORKSPACE_TOO_SMALL = -3,
     KSA_ERR_HIP = -4,                /* a HIP runtime call failed (no device, launch error, OOM)    */
@@ -48,7 +48,7 @@ typedef enum ksa_status {
 typedef struct ksa_params {
     int32_t batch;           /* B                                                               */
     int32_t n_text;          /* n: text tokens per sequence (prefill); context capacity (decode) */
-    int32_t chunk_len;       /* c: text tokens per chunk; n_text % chunk_len must be 0           */
+    int32_t chunk_len;       /* c: text tokens per chunk (an incomplete last chunk has no summaries) */
     int32_t n_summary;       /* m: summary tokens after each chunk (paper: 1); 0 = no summaries  */
     int32_t compress_ratio;  /* k = c / m; validated (k * m == c) when m > 0, ignored when m == 0 */
     int32_t window_chunks;   /* C >= 0: previous chunks whose text stays visible (Eq. 2 / Eq. 3)  */
@@ -86,7 +86,8 @@ int ksa_layout_upload(ksa_layout *layout);
 
 /* ---- introspection (host arrays, caller-allocated) used by the bit-exact layout tests ---------- */
 
-/* L = (n/c) * (c+m) augmented rows, J = n/c chunks, and the query / key tile heights of the schedule. */
+/* L = (n/c) * (c+m) + n mod c augmented rows (an incomplete last chunk has text rows only), J = n/c whole chunks,
+ * and the query / key tile heights of the schedule. */
 int ksa_layout_dims(const ksa_layout *layout, int64_t *aug_len, int32_t *n_chunks, int32_t *q_tile_rows,
                     int32_t *k_tile_rows);
 /* Eq. 1 index maps.  aug_chunk, aug_is_summary, position_ids: [L]; text_to_aug: [n]; summary_to_aug: [J*m].
@@ -196,15 +197,16 @@ int ksa_decode_fwd(const ksa_params *params /*host*/, const void *q, const void 
 
 /*
  * ksa_cache_from_prefill: hand-off from a prefilled sequence to the decode loop.  k, v: device bf16
- * [B, L, Hkv, d], the augmented sequence of n_prefill text tokens (n_prefill a multiple of chunk_len, at most
- * params->n_text; L = (n_prefill / c)(c + m)), kv_strides = {batch, row, head} in elements (NULL = contiguous).
- * Writes, per (batch, KV head), the summaries of all n_prefill / c chunks into the Summary Token Buffer and the
- * text of the last min(n_prefill / c, C + 1) chunks into the text ring of k_cache, v_cache (geometry above,
+ * [B, L, Hkv, d], the augmented sequence of n_prefill text tokens (at most params->n_text;
+ * L = (n_prefill / c)(c + m) + n_prefill mod c), kv_strides = {batch, row, head} in elements (NULL = contiguous).
+ * Writes, per (batch, KV head), the summaries of all n_prefill / c whole chunks into the Summary Token Buffer and
+ * the text of the window into the text ring of k_cache, v_cache: the incomplete last chunk, if any, and the C whole
+ * chunks before it; without an incomplete chunk the last min(n_prefill / c, C + 1) whole chunks (geometry above,
  * cache_strides = {batch, head, row}, NULL = contiguous).  Other cache rows are left as they are.  The next
  * token of every sequence is then text index n_prefill.  params->n_text is the capacity of the cache.
  * n_prefill = 0 is a no-op (k and v may be NULL then).
- * Errors: INVALID_ARG (null or misaligned pointers, n_prefill not a non-negative multiple of chunk_len,
- * strides not multiples of 8), OUT_OF_RANGE (n_prefill > n_text), HIP.
+ * Errors: INVALID_ARG (null or misaligned pointers, negative n_prefill, strides not multiples of 8),
+ * OUT_OF_RANGE (n_prefill > n_text), HIP.
  */
 int ksa_cache_from_prefill(const ksa_params *params /*host*/, int64_t n_prefill, const void *k, const void *v,
                            const int64_t kv_strides[3], void *k_cache, void *v_cache,

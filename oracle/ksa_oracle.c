@@ -50,10 +50,16 @@ int ksa_oracle_num_threads(void) { return omp_get_max_threads(); }
 /* first c slots of a chunk are text, the last m are summaries.              */
 /* ------------------------------------------------------------------------- */
 
+/*
+ * n need not be a whole number of chunks: the paper assumes divisibility to keep its notation short (Sec. 2.2),
+ * and a summary exists only once its chunk is complete (cache description, Sec. 2.3.1), so an incomplete last
+ * chunk contributes its n mod c text positions and no summaries.  Eq. 1 and Eq. 3 apply to the positions that
+ * exist; nothing else changes.
+ */
 int64_t ksa_oracle_aug_len(int64_t n, int32_t c, int32_t m)
 {
-    if (c <= 0 || m < 0 || n < 0 || n % c != 0) return -1;
-    return (n / c) * (int64_t)(c + m);
+    if (c <= 0 || m < 0 || n < 0) return -1;
+    return (n / c) * (int64_t)(c + m) + n % c;
 }
 
 /*
@@ -120,6 +126,12 @@ int ksa_oracle_index_maps(int64_t n, int32_t c, int32_t m, int32_t *aug_chunk, u
             position_ids[a] = (int32_t)(next_text - 1);
             summary_to_aug[next_summary++] = (int32_t)a;
         }
+    }
+    for (int64_t r = 0; r < n % c; ++r, ++a) {   /* the incomplete last chunk: text only */
+        aug_chunk[a] = (int32_t)(n / c);
+        aug_is_summary[a] = 0;
+        position_ids[a] = (int32_t)next_text;
+        text_to_aug[next_text++] = (int32_t)a;
     }
     return 0;
 }

@@ -343,7 +343,7 @@ def ksa_cache_from_prefill(params: ksa_params, n_prefill: int, k, v, k_cache, v_
     _require(k, "k", torch.bfloat16, 4)
     _require(v, "v", torch.bfloat16, 4)
     _check_cache(params, k_cache, v_cache)
-    L = n_prefill // max(params.chunk_len, 1) * (params.chunk_len + params.n_summary)
+    L = n_prefill // max(params.chunk_len, 1) * (params.chunk_len + params.n_summary) + n_prefill % max(params.chunk_len, 1)
     if tuple(k.shape) != (params.batch, L, params.n_kv_heads, params.head_dim) or k.shape != v.shape or \
             k.stride() != v.stride() or k.stride(3) != 1:
         raise ValueError(f"k / v shape must be {(params.batch, L, params.n_kv_heads, params.head_dim)}")

@@ -172,13 +172,13 @@ int ksa_cache_from_prefill(const ksa_params *p, int64_t n_prefill, const void *k
     int32_t s_cap = 0, rows = 0;
     const int rc = ksa_cache_geometry(p, &s_cap, &rows);
     if (rc != KSA_OK) return rc;
-    if (n_prefill < 0 || n_prefill % p->chunk_len != 0) return KSA_ERR_INVALID_ARG;
+    if (n_prefill < 0) return KSA_ERR_INVALID_ARG;
     if (n_prefill > p->n_text) return KSA_ERR_OUT_OF_RANGE;
     if (!k_cache || !v_cache || !aligned16(k_cache) || !aligned16(v_cache)) return KSA_ERR_INVALID_ARG;
     if (n_prefill == 0) return KSA_OK;   // nothing to hand over (k and v may be NULL then)
     if (!k || !v || !aligned16(k) || !aligned16(v)) return KSA_ERR_INVALID_ARG;
     KsaCacheFillLaunch a;
-    const int64_t L = n_prefill / p->chunk_len * (int64_t)(p->chunk_len + p->n_summary);
+    const int64_t L = n_prefill / p->chunk_len * (int64_t)(p->chunk_len + p->n_summary) + n_prefill % p->chunk_len;
     if (kv_strides) {
         for (int x = 0; x < 3; ++x) a.kv_strides[x] = kv_strides[x];
     } else {   // contiguous [B, L, Hkv, d]: {batch, row, head}

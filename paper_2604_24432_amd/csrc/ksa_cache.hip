@@ -18,13 +18,15 @@ struct FillArgs {
     int32_t n_chunks;          // J: whole chunks in the prefilled sequence
     int32_t n_sum_rows;        // J * m
     int32_t first_text_chunk;  // first chunk copied into the ring
+    int32_t first_text_index;  // = first_text_chunk * c
     int32_t n_rows;            // rows copied per (batch, head): n_sum_rows + text rows
     int32_t chunks16;          // 16-byte pieces per row (d / 8)
 };
 
 // One thread moves one 16-byte piece of one row of K and of V.  Row x of the copy list: x < J m is summary ordinal x
-// (augmented row (x / m)(c + m) + c + x % m, cache row x); the others are the text of the last chunks in order
-// (text index i: augmented row (i / c)(c + m) + i % c, cache row s_cap + ((i / c) mod (C + 1)) c + i % c).
+// (augmented row (x / m)(c + m) + c + x % m, cache row x); the others are the text of the window in order, up to the
+// last prefilled token (text index i: augmented row (i / c)(c + m) + i % c, cache row
+// s_cap + ((i / c) mod (C + 1)) c + i % c).
 __global__ __launch_bounds__(256) void ksa_cache_fill_kernel(const FillArgs a) {
     const int per_block = 256 / a.chunks16;
     const int x = blockIdx.x * per_block + threadIdx.x / a.chunks16;
@@ -37,8 +39,8 @@ __global__ __launch_bounds__(256) void ksa_cache_fill_kernel(const FillArgs a) {
         src_row = (int64_t)j * (a.c + a.m) + a.c + u;
         dst_row = x;
     } else {
-        const int t = x - a.n_sum_rows;
-        const int j = a.first_text_chunk + t / a.c, r = t % a.c;
+        const int i = a.first_text_index + (x - a.n_sum_rows);
+        const int j = i / a.c, r = i - j * a.c;
         src_row = (int64_t)j * (a.c + a.m) + r;
         dst_row = a.s_cap + (j % (a.C + 1)) * a.c + r;
     }
@@ -87,9 +89,12 @@ int ksa_launch_cache_fill(const KsaCacheFillLaunch &L, void *stream) {
     a.c = L.p.chunk_len, a.m = L.p.n_summary, a.C = L.p.window_chunks, a.s_cap = L.summary_capacity;
     a.n_chunks = (int32_t)(L.n_prefill / L.p.chunk_len);
     a.n_sum_rows = a.n_chunks * a.m;
-    const int ring = a.C + 1;
-    a.first_text_chunk = a.n_chunks > ring ? a.n_chunks - ring : 0;
-    a.n_rows = a.n_sum_rows + (a.n_chunks - a.first_text_chunk) * a.c;
+    // the ring holds C + 1 chunks: an incomplete last chunk takes one slot, so only the C whole chunks before it fit
+    const int tail = (int)(L.n_prefill % L.p.chunk_len);
+    const int whole_in_ring = tail > 0 ? a.C : a.C + 1;
+    a.first_text_chunk = a.n_chunks > whole_in_ring ? a.n_chunks - whole_in_ring : 0;
+    a.first_text_index = a.first_text_chunk * a.c;
+    a.n_rows = a.n_sum_rows + (int32_t)(L.n_prefill - a.first_text_index);
     a.chunks16 = L.p.head_dim / 8;
     if (a.n_rows == 0) return KSA_OK;
     const int per_block = 256 / a.chunks16;

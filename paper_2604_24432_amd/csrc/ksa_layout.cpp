@@ -149,11 +149,11 @@ int ksa_validate_params(const ksa_params *p) {
     if (p->batch <= 0 || p->n_text <= 0 || p->chunk_len <= 0 || p->n_summary < 0 || p->window_chunks < 0)
         return KSA_ERR_INVALID_ARG;
     if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_q_heads % p->n_kv_heads != 0) return KSA_ERR_INVALID_ARG;
-    if (p->n_text % p->chunk_len != 0) return KSA_ERR_INVALID_ARG;
     if (p->n_summary > 0 && (int64_t)p->compress_ratio * p->n_summary != p->chunk_len) return KSA_ERR_INVALID_ARG;
     if (p->flags & ~KSA_FLAG_SUMMARY_SELF_ONLY) return KSA_ERR_INVALID_ARG;
     if (!(p->softmax_scale == p->softmax_scale)) return KSA_ERR_INVALID_ARG;  // NaN
-    const int64_t L = (int64_t)(p->n_text / p->chunk_len) * (p->chunk_len + p->n_summary);
+    // an incomplete last chunk has text positions only (its summaries do not exist yet)
+    const int64_t L = (int64_t)(p->n_text / p->chunk_len) * (p->chunk_len + p->n_summary) + p->n_text % p->chunk_len;
     if (L >= (int64_t)1 << 30) return KSA_ERR_UNSUPPORTED;  // row indices are int32 on the device
     if (p->batch > 65535 || p->n_q_heads > 65535) return KSA_ERR_UNSUPPORTED;
     if (p->head_dim != 64 && p->head_dim != 128) return KSA_ERR_UNSUPPORTED;
@@ -174,7 +174,7 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
     if (lay->p.n_summary == 0) lay->p.compress_ratio = 0;
     const ksa_params &p = lay->p;
     lay->n_chunks = p.n_text / p.chunk_len;
-    lay->aug_len = (int64_t)lay->n_chunks * (p.chunk_len + p.n_summary);
+    lay->aug_len = (int64_t)lay->n_chunks * (p.chunk_len + p.n_summary) + p.n_text % p.chunk_len;
 
     for (int64_t t0 = 0; t0 < p.n_text; t0 += KSA_Q_TILE)
         lay->items.push_back(text_item(p, t0, (int32_t)std::min<int64_t>(KSA_Q_TILE, p.n_text - t0)));

@@ -42,7 +42,8 @@ class KsaConfig:
 
     @property
     def aug_len(self) -> int:
-        return self.n_chunks * (self.chunk_len + self.n_summary)
+        # an incomplete last chunk has text rows only
+        return self.n_chunks * (self.chunk_len + self.n_summary) + self.n_text % self.chunk_len
 
     @property
     def compress_ratio(self) -> int:

@@ -63,7 +63,6 @@ def test_cache_entry_points_validate_before_touching_the_gpu():
     vp = C.c_void_p
     # ksa_cache_from_prefill
     assert lib.ksa_cache_from_prefill(C.byref(p), 64, None, vp(a), None, vp(a), vp(a), None, None) == -1
-    assert lib.ksa_cache_from_prefill(C.byref(p), 63, vp(a), vp(a), None, vp(a), vp(a), None, None) == -1
     assert lib.ksa_cache_from_prefill(C.byref(p), -64, vp(a), vp(a), None, vp(a), vp(a), None, None) == -1
     assert lib.ksa_cache_from_prefill(C.byref(p), 576, vp(a), vp(a), None, vp(a), vp(a), None, None) == -5
     assert lib.ksa_cache_from_prefill(C.byref(p), 64, vp(a + 2), vp(a), None, vp(a), vp(a), None, None) == -1

@@ -53,12 +53,13 @@ def expected_fill(p, n_prefill, k):
     s_cap, rows = K.cache_geometry(p)
     kb = bits(k)                                     # [B, L, Hkv, d]
     out = np.full((p.batch, p.n_kv_heads, rows, p.head_dim), POISON, dtype=np.int16)
-    J = n_prefill // c
+    J, tail = n_prefill // c, n_prefill % c
     for u in range(J * m):
         out[:, :, u] = kb[:, aug_summary(u, c, m)]
-    for j in range(max(0, J - (Cw + 1)), J):
-        for r in range(c):
-            out[:, :, s_cap + (j % (Cw + 1)) * c + r] = kb[:, aug_text(j * c + r, c, m)]
+    # the ring has C + 1 slots; an incomplete last chunk occupies one of them
+    first = max(0, J - Cw) if tail else max(0, J - (Cw + 1))
+    for i in range(first * c, n_prefill):
+        out[:, :, s_cap + ((i // c) % (Cw + 1)) * c + i % c] = kb[:, aug_text(i, c, m)]
     return out
 
 
@@ -69,6 +70,9 @@ FILL_CASES = [  # (B, Hkv, d, n_cap, c, m, C, n_prefill)
     (1, 2, 64, 10 * 8, 8, 1, 2, 10 * 8),         # the paper's m = 1 form, cache filled to capacity
     (1, 1, 64, 6 * 16, 16, 0, 1, 4 * 16),        # no summaries
     (1, 1, 64, 6 * 16, 16, 2, 1, 0),             # nothing prefilled
+    (2, 2, 64, 16 * 16, 16, 2, 1, 5 * 16 + 7),   # an incomplete last chunk
+    (1, 2, 128, 12 * 64, 64, 8, 2, 64 + 1),      # ... right after a chunk boundary
+    (1, 1, 64, 6 * 16, 16, 2, 1, 9),             # ... and nothing else
 ]
 
 
@@ -77,7 +81,7 @@ def test_cache_from_prefill_is_the_documented_placement(case):
     B, Hkv, d, n_cap, c, m, Cw, n_prefill = case
     say(f"cache_from_prefill {case}")
     p = K.make_params(B, n_cap, c, m, Cw, Hkv, Hkv, d)
-    L = n_prefill // c * (c + m)
+    L = n_prefill // c * (c + m) + n_prefill % c
     g = torch.Generator().manual_seed(11)
     k = torch.randn((B, L, Hkv, d), generator=g).to(torch.bfloat16).cuda()
     v = torch.randn((B, L, Hkv, d), generator=g).to(torch.bfloat16).cuda()
@@ -134,24 +138,24 @@ def test_cache_append_writes_one_row_per_sequence():
     assert np.array_equal(bits(kc), want_k) and np.array_equal(bits(vc), want_v)
 
 
-LOOP_CASES = [  # (B, Hq, Hkv, d, c, m, C, chunks prefilled, chunks in total, flags)
-    (2, 4, 2, 64, 16, 2, 1, 3, 8, 0),
-    (2, 4, 2, 64, 16, 2, 1, 3, 8, K.KSA_FLAG_SUMMARY_SELF_ONLY),
-    (1, 8, 2, 128, 32, 4, 2, 1, 6, 0),
-    (1, 2, 2, 128, 8, 1, 3, 0, 12, 0),           # the paper's m = 1 form, nothing prefilled
+LOOP_CASES = [  # (B, Hq, Hkv, d, c, m, C, tokens prefilled, tokens in total, flags)
+    (2, 4, 2, 64, 16, 2, 1, 3 * 16, 8 * 16, 0),
+    (2, 4, 2, 64, 16, 2, 1, 3 * 16, 8 * 16, K.KSA_FLAG_SUMMARY_SELF_ONLY),
+    (1, 8, 2, 128, 32, 4, 2, 32, 6 * 32, 0),
+    (1, 2, 2, 128, 8, 1, 3, 0, 12 * 8, 0),        # the paper's m = 1 form, nothing prefilled
+    (2, 4, 2, 64, 16, 2, 1, 3 * 16 + 5, 7 * 16 + 9, 0),   # hand-off inside a chunk, sequence ends inside a chunk
 ]
 
 
 @pytest.mark.parametrize("case", LOOP_CASES)
 def test_generate_loop_matches_the_prefill_oracle(case):
-    B, Hq, Hkv, d, c, m, Cw, J0, J, flags = case
+    B, Hq, Hkv, d, c, m, Cw, n0, n, flags = case
     say(f"generate loop {case}")
-    n, n0 = J * c, J0 * c
     cfg = synth.KsaConfig("loop", B, Hq, Hkv, d, n, c, m, Cw, seed=77)
     q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))       # [B, L, H, d] over the whole sequence
     p = K.make_params(B, n, c, m, Cw, Hq, Hkv, d, flags=flags)
     kc, vc = poisoned_caches(p)
-    L0 = J0 * (c + m)
+    L0 = n0 // c * (c + m) + n0 % c
     K.ksa_cache_from_prefill(p, n0, k[:, :L0].contiguous(), v[:, :L0].contiguous(), kc, vc)
     rows, outs, lses = [], [], []
 
@@ -176,5 +180,12 @@ def test_generate_loop_matches_the_prefill_oracle(case):
     say(f"  {len(rows)} steps: max-abs {err.max():.3e} mean-abs {err.mean():.3e} lse max-abs {lerr.max():.3e}")
     assert np.isfinite(o_gpu).all() and np.isfinite(lse_gpu).all()
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS and lerr.max() <= LSE_ABS
-    # the cache now holds every summary and the text of the last C + 1 chunks: same as a hand-off of the whole sequence
-    assert np.array_equal(bits(kc), expected_fill(p, n, k)) and np.array_equal(bits(vc), expected_fill(p, n, v))
+    # the cache now holds every summary and the text of the window: same as a hand-off of the whole sequence, except
+    # that behind an incomplete last chunk its slot still holds the rest of the chunk it is overwriting
+    s_cap, _ = K.cache_geometry(p)
+    keep = np.ones(bits(kc).shape[2], dtype=bool)
+    if n % c:
+        slot0 = s_cap + ((n // c) % (Cw + 1)) * c
+        keep[slot0 + n % c: slot0 + c] = False
+    assert np.array_equal(bits(kc)[:, :, keep], expected_fill(p, n, k)[:, :, keep])
+    assert np.array_equal(bits(vc)[:, :, keep], expected_fill(p, n, v)[:, :, keep])

@@ -115,6 +115,11 @@ SMALL = [
     ("dense_causal", 1, 2, 2, 64, 320, 320, 0, 0),        # single chunk, no summaries
     ("one_tile", 1, 1, 1, 128, 64, 64, 8, 1),
     ("gqa8_d64", 2, 8, 1, 64, 512, 128, 16, 1),
+    # an incomplete last chunk: text rows only, no summaries for it
+    ("ragged_tail", 1, 4, 2, 128, 600, 64, 8, 1),
+    ("ragged_tail_short", 2, 2, 2, 64, 100, 64, 8, 1),
+    ("ragged_tail_m1", 1, 2, 1, 128, 1003, 8, 1, 16),
+    ("less_than_a_chunk", 1, 2, 2, 128, 37, 64, 8, 1),
 ]
 
 
@@ -173,6 +178,7 @@ MEDIUM = [
     ("paper_form_8k", 1, 4, 4, 128, 8192, 8, 1, 128, 0.01),
     ("sliding_8k", 1, 2, 1, 128, 8192, 64, 0, 7, 0.0),
     ("dense_4k", 1, 2, 2, 128, 4096, 4096, 0, 0, 0.01),
+    ("ragged_8k", 1, 4, 2, 128, 8192 + 37, 64, 8, 1, 0.0),
 ]
 
 

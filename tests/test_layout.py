@@ -20,6 +20,8 @@ SHAPES = [  # (n, c, m, C)
     (384, 64, 8, 0), (384, 64, 8, 2), (640, 128, 16, 1), (320, 64, 8, 9),
     (200, 8, 1, 3), (200, 8, 1, 128), (300, 20, 5, 1), (252, 12, 3, 2), (96, 96, 0, 0), (256, 16, 0, 2),
     (1024, 8, 1, 16),
+    # an incomplete last chunk (text positions only)
+    (100, 64, 8, 1), (7, 2, 1, 1), (300, 64, 8, 2), (1000, 128, 16, 1), (45, 8, 1, 3), (5, 8, 1, 1),
 ]
 
 
@@ -167,7 +169,6 @@ def test_decode_ranges_hold_exactly_the_visible_set(shape):
 
 def test_bad_arguments_are_reported_without_a_gpu():
     bad = [
-        dict(n_text=100, chunk_len=64),                 # n % c != 0
         dict(n_summary=8, compress_ratio=4),            # k * m != c
         dict(n_q_heads=3, n_kv_heads=2),                # Hq % Hkv != 0
         dict(batch=0), dict(window_chunks=-1), dict(n_summary=-1), dict(flags=2),

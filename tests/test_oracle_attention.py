@@ -259,3 +259,18 @@ def test_bad_arguments_are_rejected():
     q, k, v = rand_qkv(1, 9, 2, 2, 4, seed=1)
     with pytest.raises(ValueError):
         O.prefill(q, k, v, n=8, c=8, m=1, Cw=0, rows=[9])  # row out of range
+
+
+def test_ragged_prefill_is_the_leading_part_of_the_whole_chunk_prefill():
+    """Rows of an incomplete-last-chunk sequence see exactly what the same rows of the sequence extended to whole
+    chunks see, so outputs and log-sum-exps must agree to the last bit."""
+    rng = np.random.default_rng(5)
+    for (n, c, m, Cw) in [(7, 2, 1, 1), (21, 8, 2, 1), (37, 16, 4, 0), (50, 8, 1, 3)]:
+        n_up = (n + c - 1) // c * c
+        L, L_up = O.aug_len(n, c, m), O.aug_len(n_up, c, m)
+        q = rng.standard_normal((2, L_up, 4, 16)).astype(np.float32)
+        k = rng.standard_normal((2, L_up, 2, 16)).astype(np.float32)
+        v = rng.standard_normal((2, L_up, 2, 16)).astype(np.float32)
+        o_up, lse_up = O.prefill(q, k, v, n_up, c, m, Cw)
+        o, lse = O.prefill(q[:, :L].copy(), k[:, :L].copy(), v[:, :L].copy(), n, c, m, Cw)
+        assert np.array_equal(o, o_up[:, :L]) and np.array_equal(lse, lse_up[:, :, :L]), (n, c, m, Cw)

@@ -99,8 +99,8 @@ def test_index_maps_match_literal_sequence():
                 assert maps["position_ids"][a] == tok[1] * c + c - 1
 
 
-def test_aug_len_rejects_ragged_and_bad_shapes():
-    assert O.aug_len(10, 4, 1) == -1      # n not divisible by c
+def test_aug_len_and_bad_shapes():
+    assert O.aug_len(10, 4, 1) == 12      # two whole chunks with a summary each, two text tokens of the third
     assert O.aug_len(8, 0, 1) == -1
     assert O.aug_len(8, 4, -1) == -1
     assert O.aug_len(0, 4, 1) == 0
@@ -187,3 +187,36 @@ def test_special_cases_of_the_mask():
         want = np.array([[1 if max(0, i // c - Cw) * c <= ik <= i else 0 for ik in range(n)] for i in range(n)],
                         np.uint8)
         assert np.array_equal(O.mask(n, c, 0, Cw), want)
+
+
+# --------------------------------------------------------------------------------------
+# An incomplete last chunk (n not a multiple of c): it has text positions only.  Visibility depends on positions at
+# or before the query alone, so everything about the shorter sequence must be the leading part of the same thing for
+# the sequence extended to whole chunks, which the tests above pin.
+# --------------------------------------------------------------------------------------
+RAGGED = [(7, 2, 1, 1), (9, 4, 2, 1), (100, 64, 8, 1), (70, 64, 8, 0), (150, 20, 5, 2), (45, 8, 1, 3), (5, 8, 1, 1)]
+
+
+@pytest.mark.parametrize("shape", RAGGED)
+@pytest.mark.parametrize("flags", [0, 1])
+def test_ragged_mask_is_the_leading_block_of_the_whole_chunk_mask(shape, flags):
+    n, c, m, C = shape
+    n_up = (n + c - 1) // c * c
+    L = O.aug_len(n, c, m)
+    assert L == (n // c) * (c + m) + n % c
+    big = O.mask(n_up, c, m, C, flags)
+    assert np.array_equal(O.mask(n, c, m, C, flags), big[:L, :L])
+    maps, maps_up = O.index_maps(n, c, m), O.index_maps(n_up, c, m)
+    for key in ("aug_chunk", "aug_is_summary", "position_ids"):
+        assert np.array_equal(maps[key], maps_up[key][:L]), key
+    assert np.array_equal(maps["text_to_aug"], maps_up["text_to_aug"][:n])
+    assert np.array_equal(maps["summary_to_aug"], maps_up["summary_to_aug"][:(n // c) * m])
+    assert not maps["aug_is_summary"][L - (n % c):].any()      # the tail is text
+
+
+def test_ragged_mask_of_the_worked_example(golden_dir):
+    """The first ten rows and columns of the printed-by-hand example (n = 8, c = 2, m = 1, C = 1) are the mask of
+    n = 7: t6 is the only position of the last chunk."""
+    (n, c, m, Cw), gold = read_golden(os.path.join(golden_dir, "mask_n8_c2_m1_C1.txt"))
+    assert (n, c, m, Cw) == (8, 2, 1, 1)
+    assert np.array_equal(O.mask(7, 2, 1, 1), gold[:10, :10])
