@@ -711,6 +711,34 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
     return __builtin_amdgcn_ballot_w64(raise) != 0;
 }
 
+// What a wave does in place of a sub-tile of a masked stretch when none of its rows sees a key of the block it would
+// take weights from nor of the block it would score (block-diagonal summary rows, window edges): no MFMA, no
+// exponential.  It keeps the pipeline state the neighbouring sub-tiles rely on: the next scores are all "masked", the
+// first RING K operands of the following block are read, and with SYNC it waits for its tile loads, meets the other
+// waves at the tile's one barrier and issues its share of the requests for the tile after next.
+template <int D, bool SYNC>
+__device__ __forceinline__ void idle_subtile(unsigned char *lds, const LaneLds &ll, f32x16 (&sv_next)[QB],
+                                             bf16x8 (&ka)[Tile<D>::RING], int k_next_off, float (&mx_out)[QB],
+                                             const TileSync<D> &sync) {
+    using T = Tile<D>;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+        for (int g = 0; g < 16; ++g) sv_next[qb][g] = -INFINITY;
+        mx_out[qb] = -INFINITY;
+    }
+    if (SYNC) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next tile have landed
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < T::NI; ++i) issue_tile_load_part<D>(sync.kg, sync.k_off[i], sync.k_dst, i);
+#pragma unroll
+        for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(sync.vg, sync.v_off[i], sync.v_dst, i);
+    }
+#pragma unroll
+    for (int x = 0; x < T::RING; ++x) ka[x] = read_k_operand<D>(lds, ll.k + k_next_off, x);
+}
+
 // PIPELINED = true: work items all of whose key runs satisfy the conditions of the pipelined loop (the scheduler
 // marks them); false: the remaining items, walked with the plain loop.  Two instantiations rather than one kernel
 // with both loops keep the register allocation of the pipelined loop free of the plain loop's temporaries.
@@ -836,6 +864,9 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
         LaneOffsets<D> off;
         if (invariant) lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
 
+        // union of the visible ranges of the wave's rows in this index space: a masked tile outside it has nothing for
+        // this wave
+        const int wlo = space == KSA_SPACE_TEXT ? wlo_t : wlo_s, whi = space == KSA_SPACE_TEXT ? whi_t : whi_s;
         if constexpr (PIPELINED) {
             // (the scheduler guarantees: lane offsets invariant over the run, seg_begin % 16 == 0, and the run's last
             // tile ends inside its index space, so every row of every tile exists)
@@ -923,6 +954,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 const unsigned long long TL0 = KSA_NOW();
                 tr.acc[12] += TL0 - TS0;
 #endif
+                // does some row of this wave see a key of the tile that starts at key k0?
+                auto wave_sees = [&](int k0) { return k0 < whi && k0 + BN > wlo; };
                 auto stretch = [&](auto masked_tag, int tn_begin, int tn_end) {
                     constexpr bool MASKED = decltype(masked_tag)::value;
 #ifdef KSA_TRACE
@@ -933,11 +966,16 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                         if (tn > 0) {
                             // ---- second sub-tile of tile tn-1: weights from sv_b, scores of the first half of tile tn into
                             // sv_a (for tn = n_tiles they come from a buffer that holds no new tile and are never used)
-                            if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                            raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur, 1,
-                                                              K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl, sync,
-                                                              key0, vis_lo, vis_span KSA_TRACE_PASS) &&
-                                    (tn < n_tiles);
+                            if (MASKED && !wave_sees(key0 - BN) && !wave_sees(key0)) {
+                                idle_subtile<D, false>(lds, ll, sv_a, ka_pre, K0 + b_nxt + HALF, mxl, sync);
+                                raise = false;
+                            } else {
+                                if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                                raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur,
+                                                                  1, K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl,
+                                                                  sync, key0, vis_lo, vis_span KSA_TRACE_PASS) &&
+                                        (tn < n_tiles);
+                            }
                             const int b_old = b_cur;
                             b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
                         }
@@ -955,10 +993,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                             sync.k_dst = k_wave + b_ld;
                             sync.v_dst = v_wave + b_ld;
                             // ---- first sub-tile of tile tn: weights from sv_a, scores of its second half into sv_b ----
-                            if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                            raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF, V0 + b_cur,
-                                                             0, K0 + b_nxt, oacc, st, ind, sl, raise_margin, mxl, sync,
-                                                             key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
+                            if (MASKED && !wave_sees(key0)) {
+                                idle_subtile<D, true>(lds, ll, sv_b, ka_pre, K0 + b_nxt, mxl, sync);
+                                raise = false;
+                            } else {
+                                if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                                raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF,
+                                                                 V0 + b_cur, 0, K0 + b_nxt, oacc, st, ind, sl, raise_margin,
+                                                                 mxl, sync, key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
+                            }
                         }
                     }
 #ifdef KSA_TRACE
@@ -981,7 +1024,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             }
         } else {
         // ================= plain loop: MASKED runs, short runs, odd chunk shapes ============================
-        const int wlo = space == KSA_SPACE_TEXT ? wlo_t : wlo_s, whi = space == KSA_SPACE_TEXT ? whi_t : whi_s;
         for (int kt = seg_begin; kt < seg_end; kt += BN) {
             const int t_lo = kt, t_hi = min(kt + BN, seg_end);
             // the wave has nothing visible in this tile (block-diagonal summary rows, window edges): skip the math
