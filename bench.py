@@ -194,6 +194,7 @@ def main():
     if not args.no_full_attention:
         del k_cache, v_cache
         out["full_attention_reference"] = full_attention_reference(cfg, q, k, v, pre_avg)
+        out["paper_shape_reference"] = paper_shape_reference(cfg)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
     print(json.dumps(out), flush=True)
@@ -219,6 +220,30 @@ def full_attention_reference(cfg, q, k, v, ksa_ms):
             "ms": round(ms, 3), "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "ksa_prefill_speedup": round(ms / ksa_ms, 2)}
+
+
+def paper_shape_reference(cfg):
+    """Not part of the timed step: the paper's own chunk form at the same length and heads (one summary per chunk of 8
+    text tokens, 128 chunks of sliding window: Table of model hyper-parameters), through the same library."""
+    import torch
+    import paper_2604_24432_amd as K
+    from paper_2604_24432_amd import synth
+    pc = synth.KsaConfig("paper_shape_128k", cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_text, 8, 1, 128,
+                         seed=cfg.seed + 50)
+    p = K.make_params(pc.batch, pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks, pc.n_q_heads, pc.n_kv_heads,
+                      pc.head_dim)
+    lay = K.ksa_build_layout(p)
+    lay.upload()
+    q, k, v = synth.make_prefill_inputs(pc, device="cuda")
+    o = torch.empty_like(q)
+    lse = torch.empty((pc.batch, pc.n_q_heads, pc.aug_len), dtype=torch.float32, device="cuda")
+    ws = torch.empty(K.prefill_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+    K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws)
+    ms = float(np.mean(time_events(lambda: K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws), 5)))
+    flops = 4.0 * pc.head_dim * pc.batch * pc.n_q_heads * live_pairs(pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks)
+    return {"workload": f"B{pc.batch} Hq{pc.n_q_heads} Hkv{pc.n_kv_heads} d{pc.head_dim} n{pc.n_text} c8 m1 C128, L={pc.aug_len}",
+            "ms": round(ms, 3), "live_flops": flops, "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
 def cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args):
