@@ -133,6 +133,40 @@ def test_small_shapes(case, flags):
     full_compare(cfg, flags)
 
 
+def random_shapes(count, seed):
+    """Seeded draw of small problem shapes: chunk lengths on and off the key-tile grid, several summaries per chunk
+    or none, windows from 0 to beyond the sequence, text lengths that end inside a chunk, GQA groups 1 to 8."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        c = int(rng.choice([4, 8, 16, 20, 32, 48, 64, 128, 192]))
+        k = int(rng.choice([1, 2, 4, 8]))
+        m = 0 if rng.random() < 0.2 else (c // k if c % k == 0 and c // k <= 16 else 1)
+        if m and c % m:
+            continue
+        C = int(rng.choice([0, 1, 2, 3, 7, 40]))
+        n = int(rng.integers(1, 1400))
+        if rng.random() < 0.5:
+            n = max(c, n // c * c)
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 2, 4, 8]))
+        B = int(rng.choice([1, 2]))
+        out.append((f"r{len(out)}", B, Hkv * g, Hkv, d, n, c, m, C))
+    return out
+
+
+RANDOM = random_shapes(28, seed=20240607)
+
+
+@pytest.mark.parametrize("case", RANDOM, ids=[s[0] for s in RANDOM])
+def test_random_small_shapes(case):
+    name, B, Hq, Hkv, d, n, c, m, C = case
+    cfg = synth.KsaConfig(name, B, Hq, Hkv, d, n, c, m, C, seed=5000 + int(name[1:]),
+                          key_outlier_frac=0.02 if int(name[1:]) % 3 == 0 else 0.0)
+    full_compare(cfg, flags=K.KSA_FLAG_SUMMARY_SELF_ONLY if (int(name[1:]) % 4 == 1 and m > 1) else 0)
+
+
 def test_explicit_scale_and_strided_inputs():
     cfg = synth.KsaConfig("strided", 2, 4, 2, 128, 384, 64, 8, 1, seed=77)
     q, k, v = synth.make_prefill_inputs(cfg)
