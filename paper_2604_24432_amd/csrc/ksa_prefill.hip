@@ -129,8 +129,9 @@ struct Tile {
     static constexpr int KS = D / 16;          // k steps of the score MFMA
     static constexpr int DB = D / 32;          // 32-column blocks of the output
     static constexpr int BYTES = BN * D * 2;
-    // pipelined loop: LDS operand reads are issued this many k steps (two MFMAs each) ahead of their use
-    static constexpr int RING = KS / 4 > 2 ? KS / 4 : 2;
+    // pipelined loop: LDS operand reads are issued this many k steps (two MFMAs each) ahead of their use (measured:
+    // four steps are 1 % faster than two; more would not fit into the 256 VGPRs next to the scores and the Q operand)
+    static constexpr int RING = KS / 2 > 2 ? KS / 2 : 2;
 };
 
 // Per-lane element offsets (relative to the tile's first row) of the 16-byte pieces this lane fetches.
