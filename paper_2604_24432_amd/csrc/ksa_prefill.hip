@@ -677,7 +677,10 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                 const unsigned long long T2b = KSA_NOW();
                 tr.acc[1] += T2b - T2;
 #endif
-                __syncthreads();                      // ... and everyone's; nobody still reads the buffers loaded next
+                // ... and everyone's; nobody still reads the buffer loaded next.  A bare s_barrier: __syncthreads() would
+                // also drain this wave's LDS operand reads in flight (lgkmcnt(0)), which belong to the current tile and
+                // may stay in flight.  The "memory" clobber keeps the reads of the published tile behind it.
+                asm volatile("s_barrier" ::: "memory");
 #ifdef KSA_TRACE
                 T3 = KSA_NOW();
                 tr.acc[2] += T3 - T2b;
@@ -981,11 +984,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                             b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
                         }
                         if (tn < n_tiles) {
-                            // The tile loads bypass the compiler's bookkeeping but share the hardware counter with
-                            // everything it loads itself (register reloads from scratch around this loop).  An explicit
-                            // vmcnt(0) here, where only the loads of tile tn+1 are in flight and are about to be needed
-                            // anyway, keeps it from placing its own wait further down, behind the requests for tile tn+2.
-                            __builtin_amdgcn_s_waitcnt(0x0F70);
+                            // (no wait for the loads of tile tn+1 here: they get until the barrier inside the sub-tile)
                             // the tile after next; past the end of the run the last tile is requested again (into a free
                             // buffer)
                             const int t_ld = tn + 2 < n_tiles ? tn + 2 : n_tiles - 1;
