@@ -46,13 +46,7 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T *
 
-#ifndef KSA_PIN
-#define KSA_PIN 1
-#endif
-#ifndef KSA_NW
-#define KSA_NW 4
-#endif
-constexpr int NW = KSA_NW;                    // waves per workgroup
+constexpr int NW = 4;                         // waves per workgroup: one per SIMD
 constexpr int RW = KSA_K_TILE / NW;           // rows of a key tile each wave fetches
 constexpr int BN = KSA_K_TILE;                // keys per tile
 constexpr int QB = KSA_Q_TILE / (NW * 32);    // 32-row query blocks per wave
@@ -420,11 +414,7 @@ __device__ __forceinline__ void exp_and_pack(const f32x16 (&sacc)[QB][2], bf16x8
 // Source order below is the intended issue order: every MFMA group is followed by a slice of independent VALU
 // work, and the order is pinned with scheduling barriers, because one wave per SIMD has nobody else to fill its
 // MFMA latency.
-#if KSA_PIN
 #define KSA_STEP_FENCE() __builtin_amdgcn_sched_barrier(0)
-#else
-#define KSA_STEP_FENCE()
-#endif
 
 template <int D>
 __device__ __forceinline__ bf16x8 read_k_operand(const unsigned char *lds, int lk, int s) {
