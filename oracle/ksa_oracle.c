@@ -27,10 +27,15 @@
  * (single chunk / window covering everything), chunk-aligned sliding windows
  * (Eq. 2), hand-derived masks (tests/golden), closed-form visible counts,
  * softmax invariants, decode == last prefill row, and a pure-Python brute force.
+ * The gradients (ksa_oracle_prefill_bwd) are pinned in tests/test_oracle_bwd.py by
+ * central differences of this file's own forward pass (every term of the
+ * derivative is exercised), by an automatic-differentiation library on the same
+ * masked softmax, and by the closed form for a row with a single visible key.
  *
  * Layouts (row-major, contiguous):
  *   prefill  q [B, L, Hq, d]   k, v [B, L, Hkv, d]   float32 (exact bf16 values)
  *            o [B, R, Hq, d]   lse [B, Hq, R]         float64, R = rows requested
+ *   backward g [B, L, Hq, d] float32 (upstream gradient); dq like q, dk / dv like k, float64
  *   decode   q [B, Hq, d]; k_sum, v_sum [B, Hkv, S, d]; k_txt, v_txt [B, Hkv, W, d]
  *            text slot t of sequence b holds text index txt_base[b] + t
  */
@@ -243,6 +248,123 @@ int ksa_oracle_row_weights(const float *q, const float *k, int32_t B, int64_t n,
     free(score);
     if (lse_out) *lse_out = l;
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gradients of the prefill attention (the paper's block-sparse kernel is    */
+/* its training kernel as well, section 2.3.2 and the efficiency appendix).  */
+/* The paper prints no backward formula; this is the derivative of the       */
+/* definition above, written out.  For an upstream gradient G = dLoss/dO:    */
+/*   p_ij   = softmax weight of key j for query i (0 where masked)           */
+/*   dV_j   = sum_i p_ij G_i                                                 */
+/*   g_ij   = G_i . v_j                       (dLoss/dp_ij)                  */
+/*   ds_ij  = p_ij (g_ij - sum_l p_il g_il)   (softmax Jacobian, row i)      */
+/*   dQ_i   = scale sum_j ds_ij k_j                                          */
+/*   dK_j   = scale sum_i ds_ij q_i                                          */
+/* With grouped heads a KV head adds up the contributions of its query heads.*/
+/* ------------------------------------------------------------------------- */
+
+/*
+ * q_rows == NULL: dq holds all L rows ([B, L, Hq, d]); else the listed augmented rows ([B, n_q_rows, Hq, d]).
+ * k_rows == NULL: dk, dv hold all L rows ([B, L, Hkv, d]); else the listed rows ([B, n_k_rows, Hkv, d]).
+ * A list of length 0 (non-NULL pointer) skips that output.  g is [B, L, Hq, d] like q.
+ * Returns 0, -1 on bad arguments, -3 if memory runs out.
+ */
+int ksa_oracle_prefill_bwd(const float *q, const float *k, const float *v, const float *g, int32_t B,
+                           int64_t n, int32_t c, int32_t m, int32_t C, int32_t Hq, int32_t Hkv, int32_t d,
+                           double scale, uint32_t flags, const int64_t *q_rows, int64_t n_q_rows,
+                           const int64_t *k_rows, int64_t n_k_rows, double *dq, double *dk, double *dv)
+{
+    const int64_t L = ksa_oracle_aug_len(n, c, m);
+    if (L < 0 || B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || C < 0 || Hq % Hkv != 0) return -1;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    const int64_t RQ = q_rows ? n_q_rows : L, RK = k_rows ? n_k_rows : L;
+    for (int64_t x = 0; q_rows && x < n_q_rows; ++x)
+        if (q_rows[x] < 0 || q_rows[x] >= L) return -1;
+    for (int64_t x = 0; k_rows && x < n_k_rows; ++x)
+        if (k_rows[x] < 0 || k_rows[x] >= L) return -1;
+    const int32_t group = Hq / Hkv;
+    const int64_t kv_stride = (int64_t)Hkv * d;
+
+    /* where in the outputs an augmented row goes (-1: not asked for) */
+    int64_t *q_slot = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L > 0 ? L : 1));
+    int64_t *k_slot = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L > 0 ? L : 1));
+    if (!q_slot || !k_slot) { free(q_slot); free(k_slot); return -3; }
+    for (int64_t a = 0; a < L; ++a) q_slot[a] = q_rows ? -1 : a, k_slot[a] = k_rows ? -1 : a;
+    for (int64_t x = 0; q_rows && x < n_q_rows; ++x) q_slot[q_rows[x]] = x;
+    for (int64_t x = 0; k_rows && x < n_k_rows; ++x) k_slot[k_rows[x]] = x;
+
+    for (int64_t x = 0; x < (int64_t)B * RQ * Hq * d; ++x) dq[x] = 0.0;
+    for (int64_t x = 0; x < (int64_t)B * RK * Hkv * d; ++x) dk[x] = 0.0, dv[x] = 0.0;
+
+    int failed = 0;
+    for (int32_t b = 0; b < B && !failed; ++b)
+        for (int32_t h = 0; h < Hq && !failed; ++h) {
+            const int32_t hk = h / group;
+            const float *k_base = k + ((int64_t)b * L * Hkv + hk) * d;
+            const float *v_base = v + ((int64_t)b * L * Hkv + hk) * d;
+#pragma omp parallel
+            {
+                double *score = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+                double *weight = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+                /* this thread's share of dK, dV of head hk; added to the outputs one thread after the other */
+                double *pk = (double *)calloc((size_t)(RK > 0 ? RK : 1) * (size_t)d, sizeof(double));
+                double *pv = (double *)calloc((size_t)(RK > 0 ? RK : 1) * (size_t)d, sizeof(double));
+                if (!score || !weight || !pk || !pv) {
+#pragma omp atomic write
+                    failed = 1;
+                }
+#pragma omp barrier
+                if (!failed) {
+#pragma omp for schedule(dynamic, 4)
+                    for (int64_t aq = 0; aq < L; ++aq) {
+                        /* does anything asked for depend on this query row? */
+                        int wanted = q_slot[aq] >= 0 || !k_rows;
+                        for (int64_t x = 0; x < RK && !wanted; ++x)
+                            wanted = ksa_oracle_visible(aq, k_rows[x], c, m, C, flags);
+                        if (!wanted) continue;
+                        const float *q_row = q + (((int64_t)b * L + aq) * Hq + h) * d;
+                        const float *g_row = g + (((int64_t)b * L + aq) * Hq + h) * d;
+                        row_softmax(q_row, k_base, kv_stride, L, d, scale, aq, c, m, C, flags, score, weight);
+                        /* score[] is reused for g_ij */
+                        double inner = 0.0;
+                        for (int64_t ak = 0; ak < L; ++ak) {
+                            if (!ksa_oracle_visible(aq, ak, c, m, C, flags)) continue;
+                            score[ak] = dot_f32_as_f64(g_row, v_base + ak * kv_stride, d);
+                            inner += weight[ak] * score[ak];
+                        }
+                        double *dq_row = q_slot[aq] >= 0 ? dq + (((int64_t)b * RQ + q_slot[aq]) * Hq + h) * d : NULL;
+                        for (int64_t ak = 0; ak < L; ++ak) {
+                            if (!ksa_oracle_visible(aq, ak, c, m, C, flags)) continue;
+                            const double ds = weight[ak] * (score[ak] - inner);
+                            const float *k_row = k_base + ak * kv_stride;
+                            if (dq_row)
+                                for (int32_t t = 0; t < d; ++t) dq_row[t] += scale * ds * (double)k_row[t];
+                            if (k_slot[ak] >= 0) {
+                                double *a_k = pk + k_slot[ak] * d, *a_v = pv + k_slot[ak] * d;
+                                for (int32_t t = 0; t < d; ++t) {
+                                    a_k[t] += scale * ds * (double)q_row[t];
+                                    a_v[t] += weight[ak] * (double)g_row[t];
+                                }
+                            }
+                        }
+                    }
+#pragma omp critical
+                    for (int64_t x = 0; x < RK; ++x) {
+                        double *o_k = dk + (((int64_t)b * RK + x) * Hkv + hk) * d;
+                        double *o_v = dv + (((int64_t)b * RK + x) * Hkv + hk) * d;
+                        for (int32_t t = 0; t < d; ++t) o_k[t] += pk[x * d + t], o_v[t] += pv[x * d + t];
+                    }
+                }
+                free(score);
+                free(weight);
+                free(pk);
+                free(pv);
+            }
+        }
+    free(q_slot);
+    free(k_slot);
+    return failed ? -3 : 0;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -34,6 +34,9 @@ def lib():
         L.ksa_oracle_prefill.restype = C.c_int
         L.ksa_oracle_prefill.argtypes = [p, p, p, i32, i64, i32, i32, i32, i32, i32, i32, f64, u32,
                                          p, i64, p, p]
+        L.ksa_oracle_prefill_bwd.restype = C.c_int
+        L.ksa_oracle_prefill_bwd.argtypes = [p, p, p, p, i32, i64, i32, i32, i32, i32, i32, i32, f64, u32,
+                                             p, i64, p, i64, p, p, p]
         L.ksa_oracle_row_weights.restype = C.c_int
         L.ksa_oracle_row_weights.argtypes = [p, p, i32, i64, i32, i32, i32, i32, i32, i32, f64, u32,
                                              i32, i32, i64, p, p]
@@ -115,6 +118,35 @@ def prefill(q, k, v, n, c, m, Cw, scale=0.0, flags=0, rows=None):
     if rc != 0:
         raise ValueError(f"ksa_oracle_prefill rejected its arguments (rc={rc})")
     return o, lse
+
+
+def prefill_bwd(q, k, v, g, n, c, m, Cw, scale=0.0, flags=0, q_rows=None, k_rows=None):
+    """Gradients of sum(g * O) with respect to q, k, v.  q, g [B, L, Hq, d]; k, v [B, L, Hkv, d].
+    Returns dq [B, RQ, Hq, d], dk, dv [B, RK, Hkv, d] in float64; RQ / RK = L, or the number of listed
+    augmented rows (an empty list skips that output)."""
+    q, k, v, g = _f32(q), _f32(k), _f32(v), _f32(g)
+    B, L, Hq, d = q.shape
+    Hkv = k.shape[2]
+    assert L == aug_len(n, c, m), (L, n, c, m)
+    assert k.shape == (B, L, Hkv, d) and v.shape == k.shape and g.shape == q.shape
+
+    def rows_of(rows):
+        if rows is None:
+            return L, None, None
+        arr = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1))
+        keep = arr if arr.size else np.zeros(1, np.int64)   # a valid pointer also for an empty list
+        return arr.shape[0], keep, _ptr(keep)
+
+    RQ, q_arr, q_p = rows_of(q_rows)
+    RK, k_arr, k_p = rows_of(k_rows)
+    dq = np.zeros((B, RQ, Hq, d), np.float64)
+    dk = np.zeros((B, RK, Hkv, d), np.float64)
+    dv = np.zeros((B, RK, Hkv, d), np.float64)
+    rc = lib().ksa_oracle_prefill_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(g), B, n, c, m, Cw, Hq, Hkv, d,
+                                      float(scale), flags, q_p, RQ, k_p, RK, _ptr(dq), _ptr(dk), _ptr(dv))
+    if rc != 0:
+        raise ValueError(f"ksa_oracle_prefill_bwd rejected its arguments (rc={rc})")
+    return dq, dk, dv
 
 
 def row_weights(q, k, n, c, m, Cw, b, h, aq, scale=0.0, flags=0):
