@@ -150,6 +150,30 @@ int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void
 int ksa_prefill_relayout_v(ksa_layout *layout, const void *v, const int64_t kv_strides[3], void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* Bytes of device scratch memory ksa_prefill_bwd needs for this layout (0 for a NULL layout): one fp32 per
+ * (batch, query head, augmented row). */
+size_t ksa_prefill_bwd_workspace_bytes(const ksa_layout *layout);
+
+/*
+ * ksa_prefill_bwd: gradients of ksa_prefill_fwd's output with respect to q, k and v for an upstream gradient
+ * d_o = dLoss/dO (the paper's block-sparse kernel is its training kernel too, section 2.3.2; the formulas are
+ * the derivative of the attention definition):
+ *   P = exp(Q K^T * scale - lse) on visible pairs (Eq. 3), dV = P^T dO, dS = P o (dO V^T - rowsum(dO o O)),
+ *   dQ = scale * dS K, dK = scale * dS^T Q; with grouped heads a KV head sums over its query heads.
+ *   q, k, v, o, lse: what ksa_prefill_fwd read and wrote (same shapes, o_strides for o AND d_o; lse is required);
+ *   d_o [B, L, Hq, d], dq [B, L, Hq, d], dk and dv [B, L, Hkv, d]: device, bf16, last dim contiguous;
+ *   dq_strides for dq, dkv_strides for dk and dv ({batch, row, head}, NULL = contiguous).  Every row of dq, dk
+ *   and dv is written.
+ *   workspace: device memory, 16-byte aligned, at least ksa_prefill_bwd_workspace_bytes(layout) bytes, owned by
+ *   the caller, overwritten, needed until the work enqueued on `stream` has finished.
+ * No atomics: results do not depend on the launch order.  head_dim 64 or 128.
+ * Errors: INVALID_ARG (null or misaligned pointers, bad strides), WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP.
+ */
+int ksa_prefill_bwd(ksa_layout *layout, const void *q, const void *k, const void *v, const void *o, const float *lse,
+                    const void *d_o, void *dq, void *dk, void *dv, const int64_t q_strides[3],
+                    const int64_t kv_strides[3], const int64_t o_strides[3], const int64_t dq_strides[3],
+                    const int64_t dkv_strides[3], void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- decode over the summary KV cache (section 2.3.1) ------------------------------------------ */
 
 /*

@@ -69,6 +69,9 @@ def lib():
         "ksa_prefill_workspace_bytes": (C.c_size_t, [vp]),
         "ksa_prefill_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64p, i64p, i64p, vp, C.c_size_t, vp]),
         "ksa_prefill_relayout_v": (C.c_int, [vp, vp, i64p, vp, C.c_size_t, vp]),
+        "ksa_prefill_bwd_workspace_bytes": (C.c_size_t, [vp]),
+        "ksa_prefill_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64p, i64p, i64p, i64p, i64p, vp,
+                                      C.c_size_t, vp]),
         "ksa_cache_geometry": (C.c_int, [pp, i32p, i32p]),
         "ksa_cache_text_row": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_cache_summary_row": (C.c_int, [pp, C.c_int64, i32p]),
@@ -91,7 +94,8 @@ def lib():
 
 EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload", "ksa_layout_dims",
                     "ksa_layout_index_maps", "ksa_layout_row_ranges", "ksa_layout_mask_row",
-                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v", "ksa_cache_geometry", "ksa_cache_text_row",
+                    "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v",
+                    "ksa_prefill_bwd_workspace_bytes", "ksa_prefill_bwd", "ksa_cache_geometry", "ksa_cache_text_row",
                     "ksa_cache_summary_row", "ksa_decode_ranges", "ksa_decode_workspace_bytes",
                     "ksa_decode_fwd", "ksa_decode_summary_ranges", "ksa_decode_summary_fwd", "ksa_cache_from_prefill",
                     "ksa_cache_append", "ksa_status_string", "ksa_build_info")
@@ -245,6 +249,47 @@ def ksa_prefill_relayout_v(layout: Layout, v, workspace, stream=None):
     rc = lib().ksa_prefill_relayout_v(layout.handle, C.c_void_p(v.data_ptr()), _strides3(v, (0, 1, 2)),
                                       C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream))
     _check(rc, "ksa_prefill_relayout_v")
+
+
+def prefill_bwd_workspace_bytes(layout: Layout) -> int:
+    return int(lib().ksa_prefill_bwd_workspace_bytes(layout.handle))
+
+
+def ksa_prefill_bwd(layout: Layout, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None, workspace=None, stream=None):
+    """Gradients of ksa_prefill_fwd: q, o, d_o [B, L, Hq, d], k/v [B, L, Hkv, d] bf16, lse [B, Hq, L] fp32 on the GPU
+    -> dq like q, dk and dv like k.  o and d_o must share their strides."""
+    import torch
+    p = layout.params
+    for t, name in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (d_o, "d_o")):
+        _require(t, name, torch.bfloat16, 4)
+    _require(lse, "lse", torch.float32, 3)
+    if tuple(q.shape) != (p.batch, layout.aug_len, p.n_q_heads, p.head_dim) or o.shape != q.shape or d_o.shape != q.shape:
+        raise ValueError(f"q / o / d_o shape {tuple(q.shape)} does not match the layout")
+    if tuple(k.shape) != (p.batch, layout.aug_len, p.n_kv_heads, p.head_dim) or k.shape != v.shape or k.stride() != v.stride():
+        raise ValueError("k / v shape or strides do not match the layout")
+    if o.stride() != d_o.stride():
+        raise ValueError("o and d_o must have the same strides")
+    if tuple(lse.shape) != (p.batch, p.n_q_heads, layout.aug_len) or not lse.is_contiguous():
+        raise ValueError("lse must be contiguous [B, Hq, L]")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(dk) if dv is None else dv
+    for t, name in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
+        _require(t, name, torch.bfloat16, 4)
+    if dq.shape != q.shape or dk.shape != k.shape or dv.shape != k.shape or dk.stride() != dv.stride():
+        raise ValueError("dq / dk / dv shape or strides do not match q / k / v")
+    if workspace is None:
+        workspace = torch.empty(prefill_bwd_workspace_bytes(layout), dtype=torch.uint8, device=q.device)
+    if not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 GPU tensor")
+    rc = lib().ksa_prefill_bwd(layout.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+                               C.c_void_p(v.data_ptr()), C.c_void_p(o.data_ptr()), C.c_void_p(lse.data_ptr()),
+                               C.c_void_p(d_o.data_ptr()), C.c_void_p(dq.data_ptr()), C.c_void_p(dk.data_ptr()),
+                               C.c_void_p(dv.data_ptr()), _strides3(q, (0, 1, 2)), _strides3(k, (0, 1, 2)),
+                               _strides3(o, (0, 1, 2)), _strides3(dq, (0, 1, 2)), _strides3(dk, (0, 1, 2)),
+                               C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream))
+    _check(rc, "ksa_prefill_bwd")
+    return dq, dk, dv
 
 
 def cache_geometry(params: ksa_params) -> Tuple[int, int]:

@@ -114,6 +114,44 @@ int ksa_prefill_relayout_v(ksa_layout *lay, const void *v, const int64_t kv_stri
     return prefill_call(lay, v, v, v, workspace, nullptr, nullptr, kv_strides, nullptr, workspace, workspace_bytes, stream, 1);
 }
 
+size_t ksa_prefill_bwd_workspace_bytes(const ksa_layout *lay) {
+    return lay ? ksa_prefill_bwd_workspace_size(lay->p, lay->aug_len) : 0;
+}
+
+int ksa_prefill_bwd(ksa_layout *lay, const void *q, const void *k, const void *v, const void *o, const float *lse,
+                    const void *d_o, void *dq, void *dk, void *dv, const int64_t q_strides[3],
+                    const int64_t kv_strides[3], const int64_t o_strides[3], const int64_t dq_strides[3],
+                    const int64_t dkv_strides[3], void *workspace, size_t workspace_bytes, void *stream) {
+    if (!lay || !q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace) return KSA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+        return KSA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(lse) & 3u) return KSA_ERR_INVALID_ARG;
+    if (workspace_bytes < ksa_prefill_bwd_workspace_size(lay->p, lay->aug_len)) return KSA_ERR_WORKSPACE_TOO_SMALL;
+    const ksa_params &p = lay->p;
+    KsaPrefillBwdLaunch a;
+    default_strides(a.q_strides, q_strides, lay->aug_len, p.n_q_heads, p.head_dim);
+    default_strides(a.kv_strides, kv_strides, lay->aug_len, p.n_kv_heads, p.head_dim);
+    default_strides(a.o_strides, o_strides, lay->aug_len, p.n_q_heads, p.head_dim);
+    default_strides(a.dq_strides, dq_strides, lay->aug_len, p.n_q_heads, p.head_dim);
+    default_strides(a.dkv_strides, dkv_strides, lay->aug_len, p.n_kv_heads, p.head_dim);
+    if (!strides_ok(a.q_strides) || !strides_ok(a.kv_strides) || !strides_ok(a.o_strides) ||
+        !strides_ok(a.dq_strides) || !strides_ok(a.dkv_strides))
+        return KSA_ERR_INVALID_ARG;
+    const int rc = ksa_layout_upload(lay);
+    if (rc != KSA_OK) return rc;
+    a.q = q, a.k = k, a.v = v, a.o = o, a.d_o = d_o, a.lse = lse;
+    a.dq = dq, a.dk = dk, a.dv = dv;
+    a.items = static_cast<const KsaWorkItem *>(lay->d_items);
+    a.entries = static_cast<const KsaWgEntry *>(lay->d_entries);
+    a.n_entries = (int32_t)lay->entries.size();
+    a.p = p;
+    a.aug_len = lay->aug_len;
+    a.workspace = workspace;
+    a.workspace_bytes = workspace_bytes;
+    return ksa_launch_prefill_bwd(a, stream);
+}
+
 size_t ksa_decode_workspace_bytes(const ksa_params *p, int32_t n_splits) {
     if (ksa_validate_params(p) != KSA_OK || n_splits < 0) return 0;
     if (n_splits == 0) n_splits = ksa_decode_default_splits(p);

@@ -42,6 +42,22 @@ struct KsaPrefillLaunch {
 size_t ksa_prefill_workspace_size(const ksa_params &p);
 int ksa_launch_prefill(const KsaPrefillLaunch &a, void *stream);
 
+struct KsaPrefillBwdLaunch {
+    const void *q, *k, *v, *o, *d_o;
+    const float *lse;
+    void *dq, *dk, *dv;
+    int64_t q_strides[3], kv_strides[3], o_strides[3], dq_strides[3], dkv_strides[3];
+    const KsaWorkItem *items;
+    const KsaWgEntry *entries;
+    int32_t n_entries;
+    ksa_params p;
+    int64_t aug_len;
+    void *workspace;          // delta_i = dO_i . O_i per (batch, query head, row), fp32
+    size_t workspace_bytes;
+};
+size_t ksa_prefill_bwd_workspace_size(const ksa_params &p, int64_t aug_len);
+int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &a, void *stream);
+
 struct KsaDecodeLaunch {
     const void *q, *k_cache, *v_cache;
     const int32_t *pos;

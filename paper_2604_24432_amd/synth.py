@@ -108,6 +108,12 @@ def make_prefill_inputs(cfg: KsaConfig, device: str = "cpu") -> Tuple[torch.Tens
     return q, k, v
 
 
+def make_upstream_gradient(cfg: KsaConfig, device: str = "cpu") -> torch.Tensor:
+    """dLoss/dO [B, L, Hq, d], bf16, N(0, 1): what a following layer would hand to the backward pass."""
+    B, L = cfg.batch, cfg.aug_len
+    return _normal_bf16((L, B, cfg.n_q_heads, cfg.head_dim), cfg.seed + 7, device).transpose(0, 1).contiguous()
+
+
 def make_decode_inputs(cfg: KsaConfig, n_summary_rows: int, n_text_rows: int, device: str = "cpu"):
     """Logical (order-free) decode operands, bf16.
 

@@ -1,0 +1,127 @@
+"""GPU parity of ksa_prefill_bwd against the CPU oracle's gradients (run with -m gpu on an MI355X).
+
+All calls go through the C ABI.  The backward kernels read what the forward kernel wrote (O and the log-sum-exp),
+as a training step would.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_24432_amd as K
+from paper_2604_24432_amd import synth
+from oracle import ksa_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+# Gradients of N(0,1) tensors under an N(0,1) upstream gradient are sums of products of a weight and a bf16 value with
+# the same roundings as in the forward pass (weights and dS rounded to bf16 before the MFMA, fp32 accumulation, bf16
+# result), so the forward bars are kept: 2e-2 on every entry and 2e-3 on the mean.  Unlike the outputs (averages,
+# below 1 in size) single gradient entries reach 5 to 10, where the rounding of the bf16 result alone is 2^-9 of
+# the entry; the per-entry bar therefore adds 2^-8 |reference|.
+MAX_ABS, MEAN_ABS, REL = 2e-2, 2e-3, 2.0 ** -8
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def params_of(cfg, flags=0, scale=0.0):
+    return K.make_params(cfg.batch, cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks,
+                         cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, softmax_scale=scale, flags=flags)
+
+
+def gpu_backward(cfg, q, k, v, g, flags=0, scale=0.0):
+    lay = K.ksa_build_layout(params_of(cfg, flags, scale))
+    qd, kd, vd, gd = q.cuda(), k.cuda(), v.cuda(), g.cuda()
+    o, lse = K.ksa_prefill_fwd(lay, qd, kd, vd)
+    dq, dk, dv = K.ksa_prefill_bwd(lay, qd, kd, vd, o, lse, gd)
+    torch.cuda.synchronize()
+    return tuple(x.float().cpu().numpy() for x in (dq, dk, dv))
+
+
+def check(got, ref, what):
+    assert np.isfinite(got).all(), what
+    err = np.abs(got.astype(np.float64) - ref)
+    say(f"  {what}: max-abs {err.max():.3e} mean-abs {err.mean():.3e} (largest entry {np.abs(ref).max():.2f})")
+    assert (err <= MAX_ABS + REL * np.abs(ref)).all(), what
+    assert err.mean() <= MEAN_ABS, what
+
+
+def full_compare(cfg, flags=0, scale=0.0):
+    say(f"backward parity {cfg.name}: B{cfg.batch} Hq{cfg.n_q_heads} Hkv{cfg.n_kv_heads} d{cfg.head_dim} "
+        f"n{cfg.n_text} c{cfg.chunk_len} m{cfg.n_summary} C{cfg.window_chunks} flags{flags}")
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    dq, dk, dv = gpu_backward(cfg, q, k, v, g, flags, scale)
+    rq, rk, rv = O.prefill_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.float().numpy(),
+                               cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks, scale=scale, flags=flags)
+    check(dq, rq, cfg.name + " dq")
+    check(dk, rk, cfg.name + " dk")
+    check(dv, rv, cfg.name + " dv")
+
+
+def test_tiny_config_full_compare():
+    full_compare(synth.CONFIGS["tiny"])
+
+
+SMALL = [
+    # name, B, Hq, Hkv, d, n, c, m, C
+    ("ragged_q_tiles", 2, 4, 2, 128, 576, 64, 8, 1),
+    ("window0", 1, 4, 4, 128, 512, 64, 8, 0),
+    ("window3", 1, 2, 1, 128, 1024, 64, 8, 3),
+    ("paper_m1_c8", 1, 4, 2, 128, 1024, 8, 1, 16),
+    ("sliding_window", 1, 2, 2, 128, 1536, 64, 0, 5),
+    ("odd_chunk", 1, 2, 2, 64, 600, 20, 5, 1),
+    ("dense_causal", 1, 2, 2, 64, 320, 320, 0, 0),
+    ("one_tile", 1, 1, 1, 128, 64, 64, 8, 1),
+    ("gqa8_d64", 2, 8, 1, 64, 512, 128, 16, 1),
+    ("ragged_tail", 1, 4, 2, 128, 600, 64, 8, 1),
+    ("ragged_tail_m1", 1, 2, 1, 128, 1003, 8, 1, 16),
+    ("less_than_a_chunk", 1, 2, 2, 128, 37, 64, 8, 1),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[s[0] for s in SMALL])
+@pytest.mark.parametrize("flags", [0, K.KSA_FLAG_SUMMARY_SELF_ONLY])
+def test_small_shapes(case, flags):
+    name, B, Hq, Hkv, d, n, c, m, C = case
+    if flags and m < 2:
+        pytest.skip("flag only matters with several summaries per chunk")
+    cfg = synth.KsaConfig(name, B, Hq, Hkv, d, n, c, m, C, seed=300 + len(name))
+    full_compare(cfg, flags)
+
+
+def test_explicit_scale_and_strided_tensors():
+    """Q, K, V cut out of one packed projection output (heads interleaved), an explicit softmax scale."""
+    cfg = synth.KsaConfig("packed_qkv", 1, 4, 2, 128, 448, 64, 8, 1, seed=77)
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    lay = K.ksa_build_layout(params_of(cfg, scale=0.11))
+    packed = torch.cat([q, k, v], dim=2).cuda()            # [B, L, Hq + 2 Hkv, d]
+    qd, kd, vd = packed[:, :, :4], packed[:, :, 4:6], packed[:, :, 6:8]
+    o = torch.empty((1, cfg.aug_len, 4, 128), dtype=torch.bfloat16, device="cuda")
+    o, lse = K.ksa_prefill_fwd(lay, qd, kd, vd, o=o)
+    grads = torch.zeros_like(packed)
+    K.ksa_prefill_bwd(lay, qd, kd, vd, o, lse, g.cuda(), dq=grads[:, :, :4], dk=grads[:, :, 4:6], dv=grads[:, :, 6:8])
+    torch.cuda.synchronize()
+    gn = grads.float().cpu().numpy()
+    rq, rk, rv = O.prefill_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.float().numpy(),
+                               cfg.n_text, cfg.chunk_len, cfg.n_summary, cfg.window_chunks, scale=0.11)
+    check(gn[:, :, :4], rq, "packed dq")
+    check(gn[:, :, 4:6], rk, "packed dk")
+    check(gn[:, :, 6:8], rv, "packed dv")
+
+
+def test_rejects_bad_arguments():
+    cfg = synth.CONFIGS["tiny"]
+    lay = K.ksa_build_layout(params_of(cfg))
+    q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
+    o, lse = K.ksa_prefill_fwd(lay, q, k, v)
+    g = synth.make_upstream_gradient(cfg).cuda()
+    with pytest.raises(K.KsaError):
+        K.ksa_prefill_bwd(lay, q, k, v, o, lse, g, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(ValueError):
+        K.ksa_prefill_bwd(lay, q, k, v, o, lse[:, :, :-1], g)
