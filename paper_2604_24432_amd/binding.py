@@ -209,6 +209,11 @@ def _require(t, name, dtype, ndim):
         raise ValueError(f"{name}: expected {ndim}-d {dtype} with contiguous last dim, got {t.dtype} {tuple(t.shape)}")
 
 
+def _same_strides(x, y) -> bool:
+    """Strides agree wherever they matter (a dimension of size 1 may carry any stride)."""
+    return all(sx == sy for n, sx, sy in zip(x.shape, x.stride(), y.stride()) if n > 1)
+
+
 def prefill_workspace_bytes(layout: Layout) -> int:
     return int(lib().ksa_prefill_workspace_bytes(layout.handle))
 
@@ -222,7 +227,7 @@ def ksa_prefill_fwd(layout: Layout, q, k, v, o=None, lse=None, return_lse=True, 
         _require(t, name, torch.bfloat16, 4)
     if tuple(q.shape) != (p.batch, layout.aug_len, p.n_q_heads, p.head_dim):
         raise ValueError(f"q shape {tuple(q.shape)} does not match the layout")
-    if tuple(k.shape) != (p.batch, layout.aug_len, p.n_kv_heads, p.head_dim) or k.shape != v.shape or k.stride() != v.stride():
+    if tuple(k.shape) != (p.batch, layout.aug_len, p.n_kv_heads, p.head_dim) or k.shape != v.shape or not _same_strides(k, v):
         raise ValueError("k / v shape or strides do not match the layout")
     if o is None:
         o = torch.empty_like(q)
@@ -265,9 +270,9 @@ def ksa_prefill_bwd(layout: Layout, q, k, v, o, lse, d_o, dq=None, dk=None, dv=N
     _require(lse, "lse", torch.float32, 3)
     if tuple(q.shape) != (p.batch, layout.aug_len, p.n_q_heads, p.head_dim) or o.shape != q.shape or d_o.shape != q.shape:
         raise ValueError(f"q / o / d_o shape {tuple(q.shape)} does not match the layout")
-    if tuple(k.shape) != (p.batch, layout.aug_len, p.n_kv_heads, p.head_dim) or k.shape != v.shape or k.stride() != v.stride():
+    if tuple(k.shape) != (p.batch, layout.aug_len, p.n_kv_heads, p.head_dim) or k.shape != v.shape or not _same_strides(k, v):
         raise ValueError("k / v shape or strides do not match the layout")
-    if o.stride() != d_o.stride():
+    if not _same_strides(o, d_o):
         raise ValueError("o and d_o must have the same strides")
     if tuple(lse.shape) != (p.batch, p.n_q_heads, layout.aug_len) or not lse.is_contiguous():
         raise ValueError("lse must be contiguous [B, Hq, L]")
@@ -276,7 +281,7 @@ def ksa_prefill_bwd(layout: Layout, q, k, v, o, lse, d_o, dq=None, dk=None, dv=N
     dv = torch.empty_like(dk) if dv is None else dv
     for t, name in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
         _require(t, name, torch.bfloat16, 4)
-    if dq.shape != q.shape or dk.shape != k.shape or dv.shape != k.shape or dk.stride() != dv.stride():
+    if dq.shape != q.shape or dk.shape != k.shape or dv.shape != k.shape or not _same_strides(dk, dv):
         raise ValueError("dq / dk / dv shape or strides do not match q / k / v")
     if workspace is None:
         workspace = torch.empty(prefill_bwd_workspace_bytes(layout), dtype=torch.uint8, device=q.device)

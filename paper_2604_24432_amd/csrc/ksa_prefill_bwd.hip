@@ -40,7 +40,7 @@ struct BwdArgs {
     const KsaWgEntry *entries;
     int32_t c, m, C, w;                       // chunk_len, n_summary, window_chunks, c + m
     int32_t c_shift, m_shift;
-    int32_t group, n_q_heads, n_kv_heads, self_only;
+    int32_t group, n_q_heads, n_kv_heads, self_only, batch;
     int32_t n_text, n_sum;                    // rows per index space
     int32_t sum_tiles;                        // dK/dV grid: summary-space key tiles come first (the long ones)
     int64_t aug_len;
@@ -52,10 +52,12 @@ struct BwdArgs {
 template <int D>
 __device__ __forceinline__ int swz(int row) { return (((row & 3) << 2) | ((row >> 2) & 3)) & (D / 8 - 1); }
 
-// Rows first .. first + 63 (clamped to `last`) of one index space -> LDS tile.  base points at (batch, head).
+// Rows first .. first + 63 (clamped to `last`) of one index space, of two tensors that share the row map (K and V, or
+// Q and G) -> two LDS tiles.  The bases point at (batch, head).
 template <int D>
-__device__ __forceinline__ void load_tile(const BwdArgs &a, const __bf16 *base, int64_t row_stride, int space, int first,
-                                          int last, unsigned char *tile, int wave, int lane) {
+__device__ __forceinline__ void load_tile_pair(const BwdArgs &a, const __bf16 *base0, int64_t row_stride0,
+                                               const __bf16 *base1, int64_t row_stride1, int space, int first, int last,
+                                               unsigned char *tile0, unsigned char *tile1, int wave, int lane) {
     constexpr int CH = D / 8, RPI = 64 / CH, NI = RW / RPI;
     static_assert(RW % RPI == 0 && NI >= 1, "a wave's share of a tile is a whole number of load instructions");
 #pragma unroll
@@ -64,44 +66,64 @@ __device__ __forceinline__ void load_tile(const BwdArgs &a, const __bf16 *base, 
         const int pch = lane % CH;
         int idx = first + row;
         idx = idx < last ? idx : last;
-        const __bf16 *src = base + (int64_t)aug_row(a, space, idx) * row_stride + ((pch ^ swz<D>(row)) << 3);
-        lds_direct_load_16(src, tile + (RW * wave + RPI * i) * (D * 2));
+        const int64_t arow = aug_row(a, space, idx);
+        const int col = (pch ^ swz<D>(row)) << 3;
+        lds_direct_load_16(base0 + arow * row_stride0 + col, tile0 + (RW * wave + RPI * i) * (D * 2));
+        lds_direct_load_16(base1 + arow * row_stride1 + col, tile1 + (RW * wave + RPI * i) * (D * 2));
     }
 }
 
+// Byte addresses inside an LDS tile are written as (per-lane constant XOR small constant) + constant, so that one
+// register per tile plus the instructions' immediate offsets cover every operand read.
 struct LaneLds {
-    int rows;           // plain operand read: row r, chunk (h ^ swizzle(r)); XOR (s << 5) selects k step s
-    int t_row, t_col;   // transposing read: this lane addresses tile row t_row (+ base), columns t_col .. t_col + 3
+    int rows;   // plain operand read: row r, chunk (h ^ swizzle(r)); XOR (s << 5) selects k step s
+    int cols;   // transposing read: row t_row, the 8 bytes at column t_col of chunk (t_col / 8 ^ swizzle(t_row))
 };
 
 template <int D>
 __device__ __forceinline__ LaneLds lane_lds(int lane) {
     const int r = lane & 31, h = lane >> 5, grp = lane >> 4, li = lane & 15;
+    // transposing read: lane (grp, li) supplies the address of tile row 4 (grp / 2) + li / 4, columns
+    // 16 (grp % 2) + 4 (li % 4) .. + 3, and receives rows 4 (grp / 2) .. + 3 of column 16 (grp % 2) + li
+    const int t_row = 4 * (grp >> 1) + (li >> 2), t_col = 16 * (grp & 1) + 4 * (li & 3);
     LaneLds L;
     L.rows = r * (D * 2) + ((h ^ swz<D>(r)) << 4);
-    L.t_row = 4 * (grp >> 1) + (li >> 2);
-    L.t_col = 16 * (grp & 1) + 4 * (li & 3);
+    L.cols = t_row * (D * 2) + (((t_col >> 3) ^ swz<D>(t_row)) << 4) + ((t_col & 7) << 1);
     return L;
 }
 
-// A operand [32 tile rows of block rb] x [16 head-dim columns of k step s]
+// A operand [32 tile rows of block rb] x [16 head-dim columns of k step s].  tile_rows = tile offset + LaneLds::rows
+// (tile offsets are multiples of the tile size, so the XOR below only touches the lane part).
 template <int D>
-__device__ __forceinline__ bf16x8 read_rows(const unsigned char *tile, const LaneLds &ll, int rb, int s) {
-    return *reinterpret_cast<const bf16x8 *>(tile + ((ll.rows ^ (s << 5)) + rb * 32 * (D * 2)));
+__device__ __forceinline__ bf16x8 read_rows(const unsigned char *lds, int tile_rows, int rb, int s) {
+    return *reinterpret_cast<const bf16x8 *>(lds + ((tile_rows ^ (s << 5)) + rb * 32 * (D * 2)));
 }
 
-// A operand [32 head-dim columns of block db] x [16 tile rows from R0]: lane l gets column 32 db + l % 32 and the
-// rows R0 + 4 h + (0..3), R0 + 8 + 4 h + (0..3), h = l / 32 -- the order in which a lane's registers of a 32x32
-// result block hold its rows, so that eight result registers are the matching B operand.
+// A operand [32 head-dim columns of block db] x [16 tile rows from R0, a multiple of 16]: lane l gets column
+// 32 db + l % 32 and the rows R0 + 4 h + (0..3), R0 + 8 + 4 h + (0..3), h = l / 32 -- the order in which a lane's
+// registers of a 32x32 result block hold its rows, so that eight result registers are the matching B operand.
+// tile_cols = tile offset + LaneLds::cols.  For a row R + t_row with R a multiple of 8 and t_row < 8 the swizzle is
+// swizzle(t_row) ^ ((R >> 2) & 2), and the chunk of column block db is 4 db higher: both are XORs of bits 4..7.
 template <int D>
-__device__ __forceinline__ bf16x8 read_cols(const unsigned char *tile, const LaneLds &ll, int R0, int db) {
-    auto at = [&](int R) {
-        const int row = R + ll.t_row;
-        return row * (D * 2) + (((db * 4 + (ll.t_col >> 3)) ^ swz<D>(row)) << 4) + ((ll.t_col & 7) << 1);
-    };
-    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(tile + at(R0)));
-    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(tile + at(R0 + 8)));
+__device__ __forceinline__ bf16x8 read_cols(const unsigned char *lds, int tile_cols, int R0, int db) {
+    const int x0 = (((db * 4) ^ ((R0 >> 2) & 2)) & (D / 8 - 1)) << 4;
+    const int x1 = (((db * 4) ^ (((R0 + 8) >> 2) & 2)) & (D / 8 - 1)) << 4;
+    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + ((tile_cols ^ x0) + R0 * (D * 2))));
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(lds + ((tile_cols ^ x1) + (R0 + 8) * (D * 2))));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// acc += A B for an accumulator that lives across the whole tile loop.  Inline assembly pins it to accumulation
+// registers: left to the compiler, the 128 registers of such accumulators are copied to VGPRs and back around every
+// tile.  The compiler does not know this is an MFMA and inserts none of the wait states an MFMA needs after a VALU
+// write of its operands (the s_nop) or before a VALU read of its result (see accumulators_settle()).
+__device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 &a_op, const bf16x8 &b_op) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a_op), "v"(b_op));
+}
+
+// The last mfma_acc() results reach the register file (16 passes of 4 cycles) before anything reads them.
+__device__ __forceinline__ void accumulators_settle() {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 }
 
 __device__ __forceinline__ void zero(f32x16 &x) {
@@ -154,8 +176,7 @@ __global__ __launch_bounds__(256) void ksa_bwd_delta_kernel(const BwdArgs a, int
 template <int D>
 __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     constexpr int KS = D / 16, DB = D / 32, BYTES = BN * D * 2;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * BYTES];
-    unsigned char *k_tile = lds, *v_tile = lds + BYTES;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * BYTES];   // two buffers of a K and a V tile
 
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
@@ -199,65 +220,85 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
     const float sl = a.scale_log2e;
 
-    for (int seg = 0; seg < item.n_seg; ++seg) {
-        const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
-        int elo[QB], ehi[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            int lo, hi;
-            visible_range(a, q_space, idc[qb], space, lo, hi);
-            elo[qb] = lo > seg_begin ? lo : seg_begin;
-            ehi[qb] = hi < seg_end ? hi : seg_end;
-            if (!q_valid[qb]) elo[qb] = 0x7fffffff, ehi[qb] = 0;
+    // The key tiles of all runs form one sequence; tile t sits in LDS buffer t % 2 and tile t + 1 is requested right
+    // after the barrier that publishes tile t, so its latency hides behind the math of tile t.
+    int seg = 0, kt = item.n_seg > 0 ? item.seg[0].begin : 0;
+    auto skip_empty_runs = [&]() {
+        while (seg < item.n_seg && kt >= item.seg[seg].end) {
+            ++seg;
+            if (seg < item.n_seg) kt = item.seg[seg].begin;
         }
-        for (int kt = seg_begin; kt < seg_end; kt += BN) {
-            __syncthreads();   // everybody is done with the previous tile
-            load_tile<D>(a, kbase, a.ks[1], space, kt, seg_end - 1, k_tile, wave, lane);
-            load_tile<D>(a, vbase, a.ks[1], space, kt, seg_end - 1, v_tile, wave, lane);
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
+    };
+    auto request = [&](int sg, int key0, int buf) {
+        const int space = item.seg[sg].space, last = item.seg[sg].end - 1;
+        load_tile_pair<D>(a, kbase, a.ks[1], vbase, a.ks[1], space, key0, last, lds + buf * 2 * BYTES,
+                          lds + buf * 2 * BYTES + BYTES, wave, lane);
+    };
+    skip_empty_runs();
+    int buf = 0;
+    if (seg < item.n_seg) request(seg, kt, 0);
+    int elo[QB], ehi[QB], range_seg = -1;
+    while (seg < item.n_seg) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();   // tile (seg, kt) is complete in buffer buf; everybody is done with the other buffer
+        const int cur_seg = seg, cur_kt = kt;
+        kt += BN;
+        skip_empty_runs();
+        if (seg < item.n_seg) request(seg, kt, buf ^ 1);
+        const int k_rows = buf * 2 * BYTES + ll.rows, v_rows = k_rows + BYTES, k_cols = buf * 2 * BYTES + ll.cols;
+        buf ^= 1;
+        if (range_seg != cur_seg) {
+            range_seg = cur_seg;
+            const int space = item.seg[cur_seg].space, seg_begin = item.seg[cur_seg].begin, seg_end = item.seg[cur_seg].end;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                // nothing of this tile is visible to any row of the block: skip the math (wave-uniform)
-                const bool some = elo[qb] < kt + BN && ehi[qb] > kt;
-                if (__builtin_amdgcn_ballot_w64(some) == 0) continue;
-                f32x16 sacc[2], gacc[2];
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) zero(sacc[kb]), zero(gacc[kb]);
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb) {
-                        const bf16x8 ka = read_rows<D>(k_tile, ll, kb, s);
-                        const bf16x8 va = read_rows<D>(v_tile, ll, kb, s);
-                        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[kb], 0, 0, 0);
-                        gacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[qb][s], gacc[kb], 0, 0, 0);
-                    }
-                // dS^T in the B-operand layout: lane = query, eight registers = eight keys
-                bf16x8 pb[2][2];
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int g = 0; g < 16; ++g) {
-                        const int key = kt + kb * 32 + 8 * (g / 4) + 4 * h + (g % 4);
-                        const bool vis = key >= elo[qb] && key < ehi[qb];
-                        const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[kb][g], sl, -lse2[qb])) : 0.f;
-                        pb[kb][g / 8][g % 8] = (__bf16)(p * (gacc[kb][g] - dl[qb]));
-                    }
-                // dQ^T += K^T dS^T
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int hf = 0; hf < 2; ++hf) {
-                            const bf16x8 kt_op = read_cols<D>(k_tile, ll, kb * 32 + hf * 16, db);
-                            dqacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_op, pb[kb][hf], dqacc[qb][db], 0, 0, 0);
-                        }
+                int lo, hi;
+                visible_range(a, q_space, idc[qb], space, lo, hi);
+                elo[qb] = lo > seg_begin ? lo : seg_begin;
+                ehi[qb] = hi < seg_end ? hi : seg_end;
+                if (!q_valid[qb]) elo[qb] = 0x7fffffff, ehi[qb] = 0;
             }
+        }
+        // One 32-key block at a time, both query blocks together: every operand read from LDS feeds QB MFMAs.
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 sacc[QB], gacc[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) zero(sacc[qb]), zero(gacc[qb]);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 ka = read_rows<D>(lds, k_rows, kb, s);
+                const bf16x8 va = read_rows<D>(lds, v_rows, kb, s);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb], 0, 0, 0);
+                    gacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[qb][s], gacc[qb], 0, 0, 0);
+                }
+            }
+            // dS^T in the B-operand layout: lane = query, eight registers = eight keys
+            bf16x8 pb[QB][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int g = 0; g < 16; ++g) {
+                    const int key = cur_kt + kb * 32 + 8 * (g / 4) + 4 * h + (g % 4);
+                    const bool vis = key >= elo[qb] && key < ehi[qb];
+                    const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -lse2[qb])) : 0.f;
+                    pb[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - dl[qb]));
+                }
+            // dQ^T += K^T dS^T
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 kt_op = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][db], kt_op, pb[qb][hf]);
+                }
         }
     }
 
+    accumulators_settle();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         if (!q_valid[qb]) continue;
@@ -278,14 +319,19 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
 template <int D>
 __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     constexpr int KS = D / 16, DB = D / 32, BYTES = BN * D * 2;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * BYTES];
-    __shared__ __attribute__((aligned(16))) float st_lse[BN], st_dl[BN];
-    __shared__ __attribute__((aligned(16))) int st_lo[BN], st_hi[BN];
-    unsigned char *q_tile = lds, *g_tile = lds + BYTES;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * BYTES];   // two buffers of a Q and a G tile
+    __shared__ __attribute__((aligned(16))) float st_lse[2][BN], st_dl[2][BN];
+    __shared__ __attribute__((aligned(16))) int st_lo[2][BN], st_hi[2][BN];
 
-    int t = blockIdx.x, space = KSA_SPACE_SUMMARY;
+    // Workgroup index -> (key tile, batch, KV head), the head running fastest: consecutive workgroup ids go to the
+    // XCDs round-robin, so with 8 (batch, KV head) pairs all key tiles of a head share one L2, and they walk the same
+    // query rows at about the same time (see the loop order below).  Summary-space tiles come first, oldest chunks
+    // first: their runs of query rows are the long ones.
+    const int n_bh = a.n_kv_heads * a.batch;
+    const int bh = blockIdx.x % n_bh;
+    const int hkv = bh % a.n_kv_heads, b = bh / a.n_kv_heads;
+    int t = blockIdx.x / n_bh, space = KSA_SPACE_SUMMARY;
     if (t >= a.sum_tiles) t -= a.sum_tiles, space = KSA_SPACE_TEXT;
-    const int hkv = blockIdx.y, b = blockIdx.z;
     const int n_space = space == KSA_SPACE_TEXT ? a.n_text : a.n_sum;
     const int k0 = t * KEYS_PER_WG;
     const int k1 = k0 + KEYS_PER_WG < n_space ? k0 + KEYS_PER_WG : n_space;
@@ -333,75 +379,119 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     }
     const float sl = a.scale_log2e;
 
-    for (int hq = hkv * a.group; hq < (hkv + 1) * a.group; ++hq) {
-        const __bf16 *qbase = a.q + b * a.qs[0] + hq * a.qs[2];
-        const __bf16 *gbase = a.g + b * a.os[0] + hq * a.os[2];
-        const int64_t stat = ((int64_t)b * a.n_q_heads + hq) * a.aug_len;
-        for (int run = 0; run < 2; ++run) {
-            const int q_space = run_space[run], q_end = run_end[run];
-            for (int qt = run_begin[run]; qt < q_end; qt += BN) {
-                __syncthreads();   // everybody is done with the previous tile and its row statistics
-                load_tile<D>(a, qbase, a.qs[1], q_space, qt, q_end - 1, q_tile, wave, lane);
-                load_tile<D>(a, gbase, a.os[1], q_space, qt, q_end - 1, g_tile, wave, lane);
-                if (tid < BN) {
-                    const int qi = qt + tid;
-                    int lo = 0x7fffffff, hi = 0;
-                    float l2 = 0.f, dd = 0.f;
-                    if (qi < q_end) {
-                        visible_range(a, q_space, qi, space, lo, hi);
-                        const int aq = aug_row(a, q_space, qi);
-                        l2 = a.lse[stat + aq] * 1.4426950408889634f;
-                        dd = a.delta[stat + aq];
-                    }
-                    st_lo[tid] = lo, st_hi[tid] = hi, st_lse[tid] = l2, st_dl[tid] = dd;
-                }
-                __builtin_amdgcn_s_waitcnt(0);
-                __syncthreads();
+    // The query tiles of both runs and of all query heads of the group form one sequence: per run from its LAST row
+    // downwards in tiles anchored at the run's end (every key tile of a head then meets the same query tiles in
+    // the same order, whatever its own first row is), the heads of the group innermost.  Tile t of the sequence
+    // sits in LDS buffer t % 2 with its row statistics; tile t + 1 is requested right after the barrier that
+    // publishes tile t.
+    int run_tiles[2];
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    f32x16 sacc, gacc;
-                    zero(sacc), zero(gacc);
+    for (int x = 0; x < 2; ++x) run_tiles[x] = run_end[x] > run_begin[x] ? (run_end[x] - run_begin[x] + BN - 1) / BN : 0;
+    int run = 0, ti = 0, hj = 0;
+    auto skip_empty_runs = [&]() {
+        while (run < 2 && ti >= run_tiles[run]) ++run, ti = 0;
+    };
+    auto advance = [&]() {
+        if (++hj == a.group) hj = 0, ++ti;
+        skip_empty_runs();
+    };
+    struct QTile { int head, space, first, end; };   // rows [first, end) of one index space, one query head
+    auto current = [&]() {
+        QTile q;
+        q.head = hkv * a.group + hj;
+        q.space = run_space[run];
+        q.end = run_end[run] - ti * BN;
+        q.first = q.end - BN > run_begin[run] ? q.end - BN : run_begin[run];
+        return q;
+    };
+    struct RowStats { int lo, hi; float lse2, dl; };
+    // (threads of the first wave) what the rows of a query tile need besides Q and G
+    auto fetch_stats = [&](const QTile &q) {
+        RowStats rs{0x7fffffff, 0, 0.f, 0.f};
+        const int qi = q.first + tid;
+        if (tid < BN && qi < q.end) {
+            visible_range(a, q.space, qi, space, rs.lo, rs.hi);
+            const int64_t at = ((int64_t)b * a.n_q_heads + q.head) * a.aug_len + aug_row(a, q.space, qi);
+            rs.lse2 = a.lse[at] * 1.4426950408889634f;
+            rs.dl = a.delta[at];
+        }
+        return rs;
+    };
+    auto store_stats = [&](const RowStats &rs, int buf) {
+        if (tid < BN) st_lo[buf][tid] = rs.lo, st_hi[buf][tid] = rs.hi, st_lse[buf][tid] = rs.lse2, st_dl[buf][tid] = rs.dl;
+    };
+    auto request = [&](const QTile &q, int buf) {
+        const __bf16 *qbase = a.q + b * a.qs[0] + q.head * a.qs[2];
+        const __bf16 *gbase = a.g + b * a.os[0] + q.head * a.os[2];
+        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q.space, q.first, q.end - 1, lds + buf * 2 * BYTES,
+                          lds + buf * 2 * BYTES + BYTES, wave, lane);
+    };
+    skip_empty_runs();
+    int buf = 0;
+    if (run < 2) {
+        const QTile q = current();
+        store_stats(fetch_stats(q), 0);
+        request(q, 0);
+    }
+    while (run < 2) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();   // the current tile is complete in buffer buf; everybody is done with the other buffer
+        advance();
+        const bool more = run < 2;
+        RowStats next_stats{0x7fffffff, 0, 0.f, 0.f};
+        if (more) {
+            const QTile q = current();
+            next_stats = fetch_stats(q);
+            request(q, buf ^ 1);
+        }
+        const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
+        const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
 #pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        const bf16x8 qa = read_rows<D>(q_tile, ll, qb, s);
-                        const bf16x8 ga = read_rows<D>(g_tile, ll, qb, s);
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
-                        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], gacc, 0, 0, 0);
-                    }
-                    // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
-                    bf16x8 pp[2], pd[2];
+        for (int qb = 0; qb < 2; ++qb) {
+            f32x16 sacc, gacc;
+            zero(sacc), zero(gacc);
 #pragma unroll
-                    for (int gg = 0; gg < 4; ++gg) {
-                        const int row0 = qb * 32 + 8 * gg + 4 * h;
-                        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&st_lse[row0]);
-                        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&st_dl[row0]);
-                        const int4 lo4 = *reinterpret_cast<const int4 *>(&st_lo[row0]);
-                        const int4 hi4 = *reinterpret_cast<const int4 *>(&st_hi[row0]);
-                        const int lo_e[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi_e[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 qa = read_rows<D>(lds, q_rows, qb, s);
+                const bf16x8 ga = read_rows<D>(lds, g_rows, qb, s);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
+                gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], gacc, 0, 0, 0);
+            }
+            // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
+            bf16x8 pp[2], pd[2];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int g = gg * 4 + e;
-                            const bool vis = key >= lo_e[e] && key < hi_e[e];
-                            const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[g], sl, -l4[e])) : 0.f;
-                            pp[g / 8][g % 8] = (__bf16)p;
-                            pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - d4[e]));
-                        }
-                    }
-                    // dV^T += G^T P,  dK^T += Q^T dS
+            for (int gg = 0; gg < 4; ++gg) {
+                const int row0 = qb * 32 + 8 * gg + 4 * h;
+                const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
+                const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
+                const int4 lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
+                const int4 hi4 = *reinterpret_cast<const int4 *>(&st_hi[buf][row0]);
+                const int lo_e[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi_e[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
 #pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int hf = 0; hf < 2; ++hf) {
-                            const bf16x8 gt_op = read_cols<D>(g_tile, ll, qb * 32 + hf * 16, db);
-                            const bf16x8 qt_op = read_cols<D>(q_tile, ll, qb * 32 + hf * 16, db);
-                            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt_op, pp[hf], dvacc[db], 0, 0, 0);
-                            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt_op, pd[hf], dkacc[db], 0, 0, 0);
-                        }
+                for (int e = 0; e < 4; ++e) {
+                    const int g = gg * 4 + e;
+                    const bool vis = key >= lo_e[e] && key < hi_e[e];
+                    const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[g], sl, -l4[e])) : 0.f;
+                    pp[g / 8][g % 8] = (__bf16)p;
+                    pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - d4[e]));
                 }
             }
+            // dV^T += G^T P,  dK^T += Q^T dS
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 gt_op = read_cols<D>(lds, g_cols, qb * 32 + hf * 16, db);
+                    const bf16x8 qt_op = read_cols<D>(lds, q_cols, qb * 32 + hf * 16, db);
+                    mfma_acc(dvacc[db], gt_op, pp[hf]);
+                    mfma_acc(dkacc[db], qt_op, pd[hf]);
+                }
         }
+        buf ^= 1;
+        if (more) store_stats(next_stats, buf);   // published by the barrier at the top of the next round
     }
 
+    accumulators_settle();
     if (!key_valid) return;
     __bf16 *kp = a.dk + b * a.dks[0] + (int64_t)key_aug * a.dks[1] + hkv * a.dks[2];
     __bf16 *vp = a.dv + b * a.dks[0] + (int64_t)key_aug * a.dks[1] + hkv * a.dks[2];
@@ -453,6 +543,7 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     a.group = L.p.n_q_heads / L.p.n_kv_heads;
     a.n_q_heads = L.p.n_q_heads;
     a.n_kv_heads = L.p.n_kv_heads;
+    a.batch = L.p.batch;
     a.self_only = (L.p.flags & KSA_FLAG_SUMMARY_SELF_ONLY) ? 1 : 0;
     a.n_text = L.p.n_text;
     a.n_sum = (L.p.n_text / L.p.chunk_len) * L.p.n_summary;
@@ -468,8 +559,10 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     const int64_t n_rows = (int64_t)L.p.batch * L.aug_len * L.p.n_q_heads;
     const int64_t delta_blocks = (n_rows * (L.p.head_dim / 8) + 255) / 256;
     const int text_tiles = (a.n_text + KEYS_PER_WG - 1) / KEYS_PER_WG;
-    if (delta_blocks >= ((int64_t)1 << 31) || L.p.n_kv_heads > 65535 || L.p.batch > 65535) return KSA_ERR_UNSUPPORTED;
-    const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv(a.sum_tiles + text_tiles, L.p.n_kv_heads, L.p.batch);
+    if (delta_blocks >= ((int64_t)1 << 31) || L.p.batch > 65535 ||
+        ((int64_t)a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch >= ((int64_t)1 << 31))
+        return KSA_ERR_UNSUPPORTED;
+    const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv((unsigned)((a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch));
     if (L.p.head_dim == 128) {
         hipLaunchKernelGGL(ksa_bwd_delta_kernel<128>, dim3((unsigned)delta_blocks), dim3(256), 0, st, a, n_rows);
         hipLaunchKernelGGL(ksa_bwd_dq_kernel<128>, grid_dq, block, 0, st, a);
