@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--no-full-attention", action="store_true",
                     help="skip the dense-causal reference run at the same length (about half a second of GPU time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward-only", action="store_true",
+                    help="one forward call, then only the prefill backward --steps times (for profiler runs of its kernels)")
     ap.add_argument("--decode-splits", type=int, default=0)
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 "
@@ -130,6 +132,11 @@ def main():
         prefill()
         decode()
 
+    if args.backward_only:
+        prefill()
+        print(json.dumps({"prefill_backward": prefill_backward(cfg, lay, q, k, v, o, lse, max(args.steps, 1))}), flush=True)
+        return
+
     if args.traffic_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -190,6 +197,7 @@ def main():
     if args.hot_path_only:
         print(json.dumps(out), flush=True)
         return
+    out["prefill_backward"] = prefill_backward(cfg, lay, q, k, v, o, lse, 5)
     out["cache_lifecycle"] = cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args)
     if not args.no_full_attention:
         del k_cache, v_cache
@@ -198,6 +206,31 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
     print(json.dumps(out), flush=True)
+
+
+def prefill_backward(cfg, lay, q, k, v, o, lse, steps):
+    """Not part of the timed step: dQ, dK, dV of the same 128K prefill (ksa_prefill_bwd on the forward's O and
+    log-sum-exp, N(0,1) upstream gradient).  FLOPs: five products of 2 d per live (query, key) pair (S, dP, dV, dQ, dK);
+    the two kernels recompute S and dP once each, which is not counted."""
+    import torch
+    import paper_2604_24432_amd as K
+    from paper_2604_24432_amd import synth
+    g = synth.make_upstream_gradient(cfg, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(K.prefill_bwd_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+
+    def bwd():
+        K.ksa_prefill_bwd(lay, q, k, v, o, lse, g, dq=dq, dk=dk, dv=dv, workspace=ws)
+
+    bwd()
+    ms = time_events(bwd, steps)
+    avg = float(np.mean(ms))
+    flops = 10.0 * cfg.head_dim * cfg.batch * cfg.n_q_heads * live_pairs(cfg.n_text, cfg.chunk_len, cfg.n_summary,
+                                                                         cfg.window_chunks)
+    tf = flops / (avg * 1e-3) / 1e12
+    return {"ms": round(avg, 3), "ms_min": round(float(np.min(ms)), 3), "live_flops": flops, "live_tflops": round(tf, 1),
+            "frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+            "kernels": "ksa_bwd_delta_kernel, ksa_bwd_dq_kernel, ksa_bwd_dkv_kernel (split in profiles/)"}
 
 
 def full_attention_reference(cfg, q, k, v, ksa_ms):

@@ -125,3 +125,51 @@ def test_rejects_bad_arguments():
         K.ksa_prefill_bwd(lay, q, k, v, o, lse, g, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     with pytest.raises(ValueError):
         K.ksa_prefill_bwd(lay, q, k, v, o, lse[:, :, :-1], g)
+
+
+def sampled_compare(cfg, q_rows, k_rows, what):
+    """Listed augmented rows of dq and of dk / dv against the oracle, everything else as in full_compare()."""
+    say(f"backward parity (sampled rows) {what}: {len(q_rows)} query rows, {len(k_rows)} key rows")
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    dq, dk, dv = gpu_backward(cfg, q, k, v, g)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    rq, rk, rv = O.prefill_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.float().numpy(), cfg.n_text,
+                               cfg.chunk_len, cfg.n_summary, cfg.window_chunks, q_rows=q_rows, k_rows=k_rows)
+    check(dq[:, q_rows], rq, what + " dq")
+    check(dk[:, k_rows], rk, what + " dk")
+    check(dv[:, k_rows], rv, what + " dv")
+
+
+def aug_text(cfg, i):
+    return (i // cfg.chunk_len) * (cfg.chunk_len + cfg.n_summary) + i % cfg.chunk_len
+
+
+def aug_summary(cfg, u):
+    return (u // cfg.n_summary) * (cfg.chunk_len + cfg.n_summary) + cfg.chunk_len + u % cfg.n_summary
+
+
+def test_long_query_runs_32k_two_heads():
+    """Summary keys of the first chunks collect contributions from every later text row (32K rows per head here): the
+    longest accumulation of the dK/dV kernel, checked on two heads so that the oracle finishes in seconds."""
+    cfg = synth.KsaConfig("long_runs_32k", 1, 2, 1, 128, 32768, 128, 16, 1, seed=3100)
+    n_sum = (cfg.n_text // cfg.chunk_len) * cfg.n_summary
+    k_rows = [aug_summary(cfg, 5), aug_summary(cfg, n_sum // 2 + 3), aug_summary(cfg, n_sum - 1),
+              aug_text(cfg, 0), aug_text(cfg, 20000), aug_text(cfg, cfg.n_text - 1)]
+    q_rows = [0, aug_text(cfg, 127), aug_text(cfg, 128), aug_text(cfg, 17000), aug_summary(cfg, 0),
+              aug_summary(cfg, n_sum - 1), cfg.aug_len - 17]
+    sampled_compare(cfg, q_rows, k_rows, cfg.name)
+
+
+def test_bench_shape_128k_sampled_rows():
+    """The benchmark's configuration and launch: random query rows; text keys anywhere; summary keys of the last
+    chunks (a summary key is read by every text row behind its window: the early ones would cost the oracle hours,
+    their kind of accumulation is covered by test_long_query_runs_32k_two_heads)."""
+    cfg = synth.CONFIGS["prefill_128k"]
+    rng = np.random.default_rng(4100)
+    n, n_sum = cfg.n_text, (cfg.n_text // cfg.chunk_len) * cfg.n_summary
+    q_rows = sorted(set([0, cfg.aug_len - 1] + [int(x) for x in rng.integers(0, cfg.aug_len, 10)]))
+    k_rows = [aug_text(cfg, int(x)) for x in rng.integers(0, n, 2)] + [aug_text(cfg, n - 1)] + \
+             [aug_summary(cfg, n_sum - 1 - int(x)) for x in rng.integers(0, 4 * cfg.n_summary, 2)] + \
+             [aug_summary(cfg, n_sum - 3 * cfg.n_summary)]
+    sampled_compare(cfg, q_rows, sorted(set(k_rows)), cfg.name)
