@@ -126,6 +126,8 @@ __device__ __forceinline__ void accumulators_settle() {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 }
 
+#define KSA_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 __device__ __forceinline__ void zero(f32x16 &x) {
 #pragma unroll
     for (int g = 0; g < 16; ++g) x[g] = 0.f;
@@ -446,16 +448,29 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
         }
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
+        // Source order below is the intended issue order, pinned with scheduling fences: every group of LDS reads is
+        // issued a whole block of other work ahead of the MFMAs that consume it (one wave per SIMD has nobody else
+        // to hide the LDS latency behind; left alone, the compiler puts each read right in front of its MFMA).
+        bf16x8 qa[KS], ga[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 0, s), ga[s] = read_rows<D>(lds, g_rows, 0, s);
+        KSA_FENCE();
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             f32x16 sacc, gacc;
             zero(sacc), zero(gacc);
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const bf16x8 qa = read_rows<D>(lds, q_rows, qb, s);
-                const bf16x8 ga = read_rows<D>(lds, g_rows, qb, s);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], sacc, 0, 0, 0);
-                gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], gacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kreg[s], sacc, 0, 0, 0);
+                gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[s], vreg[s], gacc, 0, 0, 0);
+            }
+            KSA_FENCE();
+            // transposed operands of the block's first 16 rows: they land while the VALU block below runs
+            bf16x8 gt[2][DB], qt[2][DB];
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                gt[0][db] = read_cols<D>(lds, g_cols, qb * 32, db);
+                qt[0][db] = read_cols<D>(lds, q_cols, qb * 32, db);
             }
             // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
             bf16x8 pp[2], pd[2];
@@ -476,16 +491,28 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
                     pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - d4[e]));
                 }
             }
+            KSA_FENCE();
+            // ... of its last 16 rows, and the next block's score operands: they land behind the MFMAs below
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                gt[1][db] = read_cols<D>(lds, g_cols, qb * 32 + 16, db);
+                qt[1][db] = read_cols<D>(lds, q_cols, qb * 32 + 16, db);
+            }
+            if (qb == 0) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 1, s), ga[s] = read_rows<D>(lds, g_rows, 1, s);
+            }
+            KSA_FENCE();
             // dV^T += G^T P,  dK^T += Q^T dS
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
+            for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const bf16x8 gt_op = read_cols<D>(lds, g_cols, qb * 32 + hf * 16, db);
-                    const bf16x8 qt_op = read_cols<D>(lds, q_cols, qb * 32 + hf * 16, db);
-                    mfma_acc(dvacc[db], gt_op, pp[hf]);
-                    mfma_acc(dkacc[db], qt_op, pd[hf]);
+                    mfma_acc(dvacc[db], gt[hf][db], pp[hf]);
+                    mfma_acc(dkacc[db], qt[hf][db], pd[hf]);
                 }
+                KSA_FENCE();
+            }
         }
         buf ^= 1;
         if (more) store_stats(next_stats, buf);   // published by the barrier at the top of the next round
