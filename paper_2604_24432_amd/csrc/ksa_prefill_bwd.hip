@@ -262,21 +262,31 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
             }
         }
         // One 32-key block at a time, both query blocks together: every operand read from LDS feeds QB MFMAs.
+        // Source order is the intended issue order, pinned with scheduling fences: every group of LDS reads is issued
+        // a whole block of other work ahead of the MFMAs that consume it.
+        bf16x8 ka[KS], va[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 0, s), va[s] = read_rows<D>(lds, v_rows, 0, s);
+        KSA_FENCE();
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             f32x16 sacc[QB], gacc[QB];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) zero(sacc[qb]), zero(gacc[qb]);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const bf16x8 ka = read_rows<D>(lds, k_rows, kb, s);
-                const bf16x8 va = read_rows<D>(lds, v_rows, kb, s);
+            for (int s = 0; s < KS; ++s)
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
-                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb], 0, 0, 0);
-                    gacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, greg[qb][s], gacc[qb], 0, 0, 0);
+                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[qb][s], sacc[qb], 0, 0, 0);
+                    gacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[s], greg[qb][s], gacc[qb], 0, 0, 0);
                 }
-            }
+            KSA_FENCE();
+            // K^T operands of this key block: they land while the VALU block below runs
+            bf16x8 kt_op[2][DB];
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) kt_op[hf][db] = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
             // dS^T in the B-operand layout: lane = query, eight registers = eight keys
             bf16x8 pb[QB][2];
 #pragma unroll
@@ -288,15 +298,20 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
                     const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -lse2[qb])) : 0.f;
                     pb[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - dl[qb]));
                 }
+            KSA_FENCE();
+            if (kb == 0) {   // the next key block's score operands land behind the MFMAs below
+#pragma unroll
+                for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 1, s), va[s] = read_rows<D>(lds, v_rows, 1, s);
+            }
+            KSA_FENCE();
             // dQ^T += K^T dS^T
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x8 kt_op = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][db], kt_op, pb[qb][hf]);
-                }
+                    for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][db], kt_op[hf][db], pb[qb][hf]);
+            KSA_FENCE();
         }
     }
 
