@@ -121,6 +121,22 @@ __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 &a_op, const 
     asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a_op), "v"(b_op));
 }
 
+// acc (+)= A B for a short-lived score block whose B operand is held in accumulation registers for the whole kernel
+// (the wave's own Q / dO or K / V rows): MFMA reads them there directly, and the vector registers stay free for the
+// operands streamed through LDS.  FIRST starts the block from zero.  Before VALU code reads acc the results have to
+// reach the register file: scores_settle().
+template <bool FIRST>
+__device__ __forceinline__ void mfma_score(f32x16 &acc, const bf16x8 &a_op, const bf16x8 &b_resident) {
+    if constexpr (FIRST)
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a_op), "a"(b_resident));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a_op), "a"(b_resident));
+}
+
+// 24 wait states: more than the 16 passes of the last mfma_score() plus the margin the ISA asks for before a VALU
+// instruction may read an MFMA result.
+__device__ __forceinline__ void scores_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
+
 // The last mfma_acc() results reach the register file (16 passes of 4 cycles) before anything reads them.
 __device__ __forceinline__ void accumulators_settle() {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
@@ -272,13 +288,16 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
         for (int kb = 0; kb < 2; ++kb) {
             f32x16 sacc[QB], gacc[QB];
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) zero(sacc[qb]), zero(gacc[qb]);
+            for (int qb = 0; qb < QB; ++qb) {
+                mfma_score<true>(sacc[qb], ka[0], qreg[qb][0]);
+                mfma_score<true>(gacc[qb], va[0], greg[qb][0]);
+            }
 #pragma unroll
-            for (int s = 0; s < KS; ++s)
+            for (int s = 1; s < KS; ++s)
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
-                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[qb][s], sacc[qb], 0, 0, 0);
-                    gacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[s], greg[qb][s], gacc[qb], 0, 0, 0);
+                    mfma_score<false>(sacc[qb], ka[s], qreg[qb][s]);
+                    mfma_score<false>(gacc[qb], va[s], greg[qb][s]);
                 }
             KSA_FENCE();
             // K^T operands of this key block: they land while the VALU block below runs
@@ -287,6 +306,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
             for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
                 for (int db = 0; db < DB; ++db) kt_op[hf][db] = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
+            scores_settle();
             // dS^T in the B-operand layout: lane = query, eight registers = eight keys
             bf16x8 pb[QB][2];
 #pragma unroll
@@ -473,11 +493,12 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             f32x16 sacc, gacc;
-            zero(sacc), zero(gacc);
+            mfma_score<true>(sacc, qa[0], kreg[0]);
+            mfma_score<true>(gacc, ga[0], vreg[0]);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kreg[s], sacc, 0, 0, 0);
-                gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[s], vreg[s], gacc, 0, 0, 0);
+            for (int s = 1; s < KS; ++s) {
+                mfma_score<false>(sacc, qa[s], kreg[s]);
+                mfma_score<false>(gacc, ga[s], vreg[s]);
             }
             KSA_FENCE();
             // transposed operands of the block's first 16 rows: they land while the VALU block below runs
@@ -487,6 +508,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
                 gt[0][db] = read_cols<D>(lds, g_cols, qb * 32, db);
                 qt[0][db] = read_cols<D>(lds, q_cols, qb * 32, db);
             }
+            scores_settle();
             // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
             bf16x8 pp[2], pd[2];
 #pragma unroll
