@@ -33,7 +33,11 @@ static_assert(BN == 64, "an LDS tile is two 32-row MFMA blocks");
 struct BwdArgs {
     const __bf16 *q, *k, *v, *o, *g;          // g: upstream gradient dLoss/dO, laid out like o
     const float *lse;                         // [B, Hq, L] natural-log sum-exp of the forward pass
-    float *delta;                             // [B, Hq, L] workspace
+    // workspace: per-row statistics in COMPACT order, [B, Hq, nt_pad + ns_pad] fp32 each: position p < nt_pad is
+    // text index p, position nt_pad + u is summary ordinal u; rows past the end of an index space hold zeros
+    float *lse2c;                             // log-sum-exp times log2(e)
+    float *dlc;                               // delta_i = dO_i . O_i
+    int32_t nt_pad, ns_pad;                   // rows per index space rounded up to 64
     __bf16 *dq, *dk, *dv;
     int64_t qs[3], ks[3], os[3], dqs[3], dks[3];   // {batch, row, head} strides in elements (os: o and g)
     const KsaWorkItem *items;
@@ -71,6 +75,13 @@ __device__ __forceinline__ void load_tile_pair(const BwdArgs &a, const __bf16 *b
         lds_direct_load_16(base0 + arow * row_stride0 + col, tile0 + (RW * wave + RPI * i) * (D * 2));
         lds_direct_load_16(base1 + arow * row_stride1 + col, tile1 + (RW * wave + RPI * i) * (D * 2));
     }
+}
+
+// global -> LDS, 4 bytes per lane: the wave's 64 pieces land back to back (lane order) from the wave-uniform LDS
+// address dst.  Inline assembly for the same reason as lds_direct_load_16().
+__device__ __forceinline__ void lds_direct_load_4(const float *src, const unsigned char *dst) {
+    const unsigned lds_addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(src), "s"(lds_addr) : "memory");
 }
 
 // Byte addresses inside an LDS tile are written as (per-lane constant XOR small constant) + constant, so that one
@@ -167,27 +178,39 @@ __device__ __forceinline__ void visible_range(const BwdArgs &a, int q_space, int
     }
 }
 
-// ---- delta_i = G_i . O_i ------------------------------------------------------------------------------------
+// ---- per-row statistics: delta_i = G_i . O_i and lse_i log2(e), in compact order ------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void ksa_bwd_delta_kernel(const BwdArgs a, int64_t n_rows /* B * L * Hq */) {
+__global__ __launch_bounds__(256) void ksa_bwd_delta_kernel(const BwdArgs a, int64_t n_slots /* B * Hq * (nt_pad + ns_pad) */) {
     constexpr int CH = D / 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    int64_t rh = idx / CH;
+    int64_t slot = idx / CH;
     const int piece = (int)(idx % CH);
-    const bool live = rh < n_rows;
-    if (!live) rh = n_rows - 1;
-    const int hq = (int)(rh % a.n_q_heads);
-    const int64_t br = rh / a.n_q_heads;
-    const int64_t aq = br % a.aug_len, b = br / a.aug_len;
-    const int64_t off = b * a.os[0] + aq * a.os[1] + hq * a.os[2] + piece * 8;
-    const bf16x8 o8 = *reinterpret_cast<const bf16x8 *>(a.o + off);
-    const bf16x8 g8 = *reinterpret_cast<const bf16x8 *>(a.g + off);
-    float s = 0.f;
+    const bool in_grid = slot < n_slots;
+    if (!in_grid) slot = n_slots - 1;
+    const int sp = a.nt_pad + a.ns_pad;
+    const int pos = (int)(slot % sp);
+    const int64_t bh = slot / sp;
+    const int hq = (int)(bh % a.n_q_heads);
+    const int64_t b = bh / a.n_q_heads;
+    const int space = pos < a.nt_pad ? KSA_SPACE_TEXT : KSA_SPACE_SUMMARY;
+    const int ci = space == KSA_SPACE_TEXT ? pos : pos - a.nt_pad;
+    const bool live = ci < (space == KSA_SPACE_TEXT ? a.n_text : a.n_sum);   // wave-uniform per group of CH lanes
+    float s = 0.f, l2 = 0.f;
+    if (live) {
+        const int64_t aq = aug_row(a, space, ci);
+        const int64_t off = b * a.os[0] + aq * a.os[1] + hq * a.os[2] + piece * 8;
+        const bf16x8 o8 = *reinterpret_cast<const bf16x8 *>(a.o + off);
+        const bf16x8 g8 = *reinterpret_cast<const bf16x8 *>(a.g + off);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s += (float)o8[e] * (float)g8[e];
+        for (int e = 0; e < 8; ++e) s += (float)o8[e] * (float)g8[e];
+        l2 = a.lse[(b * a.n_q_heads + hq) * a.aug_len + aq] * 1.4426950408889634f;
+    }
 #pragma unroll
     for (int d = CH / 2; d > 0; d >>= 1) s += __shfl_xor(s, d);
-    if (live && piece == 0) a.delta[(b * a.n_q_heads + hq) * a.aug_len + aq] = s;
+    if (in_grid && piece == 0) {
+        a.dlc[slot] = s;
+        a.lse2c[slot] = l2;
+    }
 }
 
 // ---- dQ -----------------------------------------------------------------------------------------------------
@@ -224,9 +247,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
             qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16);
             greg[qb][s] = *reinterpret_cast<const bf16x8 *>(gp + s * 16);
         }
-        const int64_t stat = ((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb];
-        lse2[qb] = a.lse[stat] * 1.4426950408889634f;
-        dl[qb] = a.delta[stat];
+        const int64_t stat = ((int64_t)b * a.n_q_heads + hq) * (a.nt_pad + a.ns_pad) +
+                             (q_space == KSA_SPACE_TEXT ? idc[qb] : a.nt_pad + idc[qb]);
+        lse2[qb] = a.lse2c[stat];
+        dl[qb] = a.dlc[stat];
     }
     f32x16 dqacc[QB][DB];
 #pragma unroll
@@ -356,9 +380,14 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
 template <int D>
 __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     constexpr int KS = D / 16, DB = D / 32, BYTES = BN * D * 2;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * BYTES];   // two buffers of a Q and a G tile
-    __shared__ __attribute__((aligned(16))) float st_lse[2][BN], st_dl[2][BN];
-    __shared__ __attribute__((aligned(16))) int st_lo[2][BN], st_hi[2][BN];
+    // tiles in flight + 1: the query tiles of a long run stream from HBM (their total is far beyond the caches), and
+    // the key tiles of a head advance in step, so every step sees the full memory latency unless the request runs
+    // several steps ahead
+    constexpr int STAGES = 4;
+    // STAGES buffers of a Q and a G tile with the tiles' row statistics
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * 2 * BYTES];
+    __shared__ __attribute__((aligned(256))) float st_lse[STAGES][BN], st_dl[STAGES][BN];
+    __shared__ __attribute__((aligned(16))) int st_lo[STAGES][BN], st_hi[STAGES][BN];
 
     // Workgroup index -> (key tile, batch, KV head), the head running fastest: consecutive workgroup ids go to the
     // XCDs round-robin, so with 8 (batch, KV head) pairs all key tiles of a head share one L2, and they walk the same
@@ -416,71 +445,65 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     }
     const float sl = a.scale_log2e;
 
-    // The query tiles of both runs and of all query heads of the group form one sequence: per run from its LAST row
-    // downwards in tiles anchored at the run's end (every key tile of a head then meets the same query tiles in
-    // the same order, whatever its own first row is), the heads of the group innermost.  Tile t of the sequence
-    // sits in LDS buffer t % 2 with its row statistics; tile t + 1 is requested right after the barrier that
-    // publishes tile t.
-    int run_tiles[2];
+    // The query tiles of both runs and of all query heads of the group form one sequence: per run the aligned 64-row
+    // blocks of the index space that overlap it, from the LAST one downwards (every key tile of a head then meets the
+    // same query tiles in the same order, whatever its own first row is), the heads of the group innermost.  Rows
+    // of a block outside the run are masked through their visible range.  Tile t of the sequence sits in LDS stage
+    // t % STAGES with its row statistics; tile t + STAGES - 1 is requested right after the barrier that publishes
+    // tile t.
+    int run_first_blk[2], run_tiles[2];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) run_tiles[x] = run_end[x] > run_begin[x] ? (run_end[x] - run_begin[x] + BN - 1) / BN : 0;
-    int run = 0, ti = 0, hj = 0;
+    for (int x = 0; x < 2; ++x) {
+        run_first_blk[x] = run_begin[x] / BN;
+        run_tiles[x] = run_end[x] > run_begin[x] ? (run_end[x] - 1) / BN - run_first_blk[x] + 1 : 0;
+    }
+    int run = 0, ti = 0, hj = 0;   // the next tile to request
     auto skip_empty_runs = [&]() {
         while (run < 2 && ti >= run_tiles[run]) ++run, ti = 0;
     };
-    auto advance = [&]() {
+    // Requests the next tile of the sequence into `stage`: every wave issues LOADS_PER_TILE loads, so that the waits
+    // below can count them.
+    constexpr int LOADS_PER_TILE = 2 * (RW / (64 / (D / 8))) + 2;
+    const int stats_stride = a.nt_pad + a.ns_pad;
+    auto request = [&](int stage) {
+        const int head = hkv * a.group + hj, q_space = run_space[run];
+        const int first = (run_first_blk[run] + run_tiles[run] - 1 - ti) * BN;
+        const __bf16 *qbase = a.q + b * a.qs[0] + head * a.qs[2];
+        const __bf16 *gbase = a.g + b * a.os[0] + head * a.os[2];
+        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, lds + stage * 2 * BYTES,
+                          lds + stage * 2 * BYTES + BYTES, wave, lane);
+        // lse and delta of the 64 rows: one 4-byte piece per lane, straight into LDS (all waves fetch the same 256
+        // bytes: keeps the per-wave load count uniform, and costs nothing)
+        const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (q_space == KSA_SPACE_TEXT ? 0 : a.nt_pad) +
+                           first + lane;
+        lds_direct_load_4(a.lse2c + at, reinterpret_cast<const unsigned char *>(&st_lse[stage][0]));
+        lds_direct_load_4(a.dlc + at, reinterpret_cast<const unsigned char *>(&st_dl[stage][0]));
+        if (tid < BN) {   // visible key range of each row (empty for rows of the block outside the run)
+            const int qi = first + tid;
+            int lo = 0x7fffffff, hi = 0;
+            if (qi >= run_begin[run] && qi < run_end[run]) visible_range(a, q_space, qi, space, lo, hi);
+            st_lo[stage][tid] = lo, st_hi[stage][tid] = hi;
+        }
         if (++hj == a.group) hj = 0, ++ti;
         skip_empty_runs();
     };
-    struct QTile { int head, space, first, end; };   // rows [first, end) of one index space, one query head
-    auto current = [&]() {
-        QTile q;
-        q.head = hkv * a.group + hj;
-        q.space = run_space[run];
-        q.end = run_end[run] - ti * BN;
-        q.first = q.end - BN > run_begin[run] ? q.end - BN : run_begin[run];
-        return q;
-    };
-    struct RowStats { int lo, hi; float lse2, dl; };
-    // (threads of the first wave) what the rows of a query tile need besides Q and G
-    auto fetch_stats = [&](const QTile &q) {
-        RowStats rs{0x7fffffff, 0, 0.f, 0.f};
-        const int qi = q.first + tid;
-        if (tid < BN && qi < q.end) {
-            visible_range(a, q.space, qi, space, rs.lo, rs.hi);
-            const int64_t at = ((int64_t)b * a.n_q_heads + q.head) * a.aug_len + aug_row(a, q.space, qi);
-            rs.lse2 = a.lse[at] * 1.4426950408889634f;
-            rs.dl = a.delta[at];
-        }
-        return rs;
-    };
-    auto store_stats = [&](const RowStats &rs, int buf) {
-        if (tid < BN) st_lo[buf][tid] = rs.lo, st_hi[buf][tid] = rs.hi, st_lse[buf][tid] = rs.lse2, st_dl[buf][tid] = rs.dl;
-    };
-    auto request = [&](const QTile &q, int buf) {
-        const __bf16 *qbase = a.q + b * a.qs[0] + q.head * a.qs[2];
-        const __bf16 *gbase = a.g + b * a.os[0] + q.head * a.os[2];
-        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q.space, q.first, q.end - 1, lds + buf * 2 * BYTES,
-                          lds + buf * 2 * BYTES + BYTES, wave, lane);
-    };
     skip_empty_runs();
-    int buf = 0;
-    if (run < 2) {
-        const QTile q = current();
-        store_stats(fetch_stats(q), 0);
-        request(q, 0);
-    }
-    while (run < 2) {
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();   // the current tile is complete in buffer buf; everybody is done with the other buffer
-        advance();
-        const bool more = run < 2;
-        RowStats next_stats{0x7fffffff, 0, 0.f, 0.f};
-        if (more) {
-            const QTile q = current();
-            next_stats = fetch_stats(q);
-            request(q, buf ^ 1);
-        }
+    int pending = 0;   // tiles requested and not yet consumed
+    for (; pending < STAGES - 1 && run < 2; ++pending) request(pending);
+    int buf = 0;       // stage of the oldest pending tile
+    while (pending > 0) {
+        // the oldest pending tile is complete when at most the loads of the younger ones are outstanding
+        if (pending >= 3)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LOADS_PER_TILE) & 15) | (((2 * LOADS_PER_TILE) >> 4) << 14));
+        else if (pending == 2)
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (LOADS_PER_TILE & 15) | ((LOADS_PER_TILE >> 4) << 14));
+        else
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();   // that tile is published; everybody is done with the stage the next request overwrites
+        if (run < 2)
+            request((buf + STAGES - 1) % STAGES);
+        else
+            --pending;
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
         // Source order below is the intended issue order, pinned with scheduling fences: every group of LDS reads is
@@ -551,8 +574,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
                 KSA_FENCE();
             }
         }
-        buf ^= 1;
-        if (more) store_stats(next_stats, buf);   // published by the barrier at the top of the next round
+        buf = (buf + 1) % STAGES;
     }
 
     accumulators_settle();
@@ -576,8 +598,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
 
 }  // namespace
 
-size_t ksa_prefill_bwd_workspace_size(const ksa_params &p, int64_t aug_len) {
-    return (size_t)((int64_t)p.batch * p.n_q_heads * aug_len * (int64_t)sizeof(float));
+namespace {
+int64_t pad64(int64_t x) { return (x + 63) / 64 * 64; }
+// fp32 slots of one statistics array: B Hq (text rows + summary rows, each rounded up to 64)
+int64_t stat_slots(const ksa_params &p) {
+    const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
+    return (int64_t)p.batch * p.n_q_heads * (pad64(p.n_text) + pad64(n_sum));
+}
+}  // namespace
+
+size_t ksa_prefill_bwd_workspace_size(const ksa_params &p, int64_t) {
+    return (size_t)(2 * stat_slots(p) * (int64_t)sizeof(float));
 }
 
 int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
@@ -588,7 +619,8 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     a.o = static_cast<const __bf16 *>(L.o);
     a.g = static_cast<const __bf16 *>(L.d_o);
     a.lse = L.lse;
-    a.delta = static_cast<float *>(L.workspace);
+    a.lse2c = static_cast<float *>(L.workspace);
+    a.dlc = a.lse2c + stat_slots(L.p);
     a.dq = static_cast<__bf16 *>(L.dq);
     a.dk = static_cast<__bf16 *>(L.dk);
     a.dv = static_cast<__bf16 *>(L.dv);
@@ -612,6 +644,8 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     a.n_text = L.p.n_text;
     a.n_sum = (L.p.n_text / L.p.chunk_len) * L.p.n_summary;
     a.sum_tiles = (a.n_sum + KEYS_PER_WG - 1) / KEYS_PER_WG;
+    a.nt_pad = (int32_t)pad64(a.n_text);
+    a.ns_pad = (int32_t)pad64(a.n_sum);
     a.aug_len = L.aug_len;
     a.scale = L.p.softmax_scale;
     a.scale_log2e = L.p.softmax_scale * 1.4426950408889634f;
@@ -620,7 +654,7 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     if (L.p.head_dim != 128 && L.p.head_dim != 64) return KSA_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const int64_t n_rows = (int64_t)L.p.batch * L.aug_len * L.p.n_q_heads;
+    const int64_t n_rows = stat_slots(L.p);
     const int64_t delta_blocks = (n_rows * (L.p.head_dim / 8) + 255) / 256;
     const int text_tiles = (a.n_text + KEYS_PER_WG - 1) / KEYS_PER_WG;
     if (delta_blocks >= ((int64_t)1 << 31) || L.p.batch > 65535 ||
