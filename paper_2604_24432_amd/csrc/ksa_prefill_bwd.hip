@@ -18,6 +18,8 @@
 // row's visible range (Eq. 3); there is no unmasked fast path yet.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ksa_device.h"
 #include "ksa_internal.h"
 
@@ -387,7 +389,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // STAGES buffers of a Q and a G tile with the tiles' row statistics
     __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * 2 * BYTES];
     __shared__ __attribute__((aligned(256))) float st_lse[STAGES][BN], st_dl[STAGES][BN];
-    __shared__ __attribute__((aligned(16))) int st_lo[STAGES][BN], st_hi[STAGES][BN];
+    __shared__ __attribute__((aligned(16))) int st_lo[STAGES][BN], st_span[STAGES][BN];   // visible keys: [lo, lo + span)
+    __shared__ int st_full[STAGES];   // 1: every row of the tile sees every key of the workgroup
 
     // Workgroup index -> (key tile, batch, KV head), the head running fastest: consecutive workgroup ids go to the
     // XCDs round-robin, so with 8 (batch, KV head) pairs all key tiles of a head share one L2, and they walk the same
@@ -482,7 +485,9 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
             const int qi = first + tid;
             int lo = 0x7fffffff, hi = 0;
             if (qi >= run_begin[run] && qi < run_end[run]) visible_range(a, q_space, qi, space, lo, hi);
-            st_lo[stage][tid] = lo, st_hi[stage][tid] = hi;
+            st_lo[stage][tid] = lo, st_span[stage][tid] = hi > lo ? hi - lo : 0;
+            const bool sees_all = lo <= k0 && hi >= k1;
+            if (tid == 0) st_full[stage] = __builtin_amdgcn_ballot_w64(sees_all) == ~0ull ? 1 : 0;
         }
         if (++hj == a.group) hj = 0, ++ti;
         skip_empty_runs();
@@ -506,6 +511,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
             --pending;
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
+        const bool tile_full = __builtin_amdgcn_readfirstlane(st_full[buf]) != 0;
         // Source order below is the intended issue order, pinned with scheduling fences: every group of LDS reads is
         // issued a whole block of other work ahead of the MFMAs that consume it (one wave per SIMD has nobody else
         // to hide the LDS latency behind; left alone, the compiler puts each read right in front of its MFMA).
@@ -532,25 +538,47 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
                 qt[0][db] = read_cols<D>(lds, q_cols, qb * 32, db);
             }
             scores_settle();
-            // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
+            // P and dS in the B-operand layout: lane = key, eight registers = eight query rows.  The statistics of the
+            // next four rows are read while the current four are worked on; a tile all of whose rows see all of the
+            // workgroup's keys (nearly every tile of a summary key) skips the visibility test.
             bf16x8 pp[2], pd[2];
+            auto weights = [&](auto masked_tag) {
+                constexpr bool MASKED = decltype(masked_tag)::value;
+                struct Stats { f32x4 l4, d4; int4 lo4, span4; };
+                auto read_stats = [&](int gg) {
+                    const int row0 = qb * 32 + 8 * gg + 4 * h;
+                    Stats st;
+                    st.l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
+                    st.d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
+                    if constexpr (MASKED) {
+                        st.lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
+                        st.span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
+                    }
+                    return st;
+                };
+                Stats nxt = read_stats(0);
 #pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                const int row0 = qb * 32 + 8 * gg + 4 * h;
-                const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
-                const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
-                const int4 lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
-                const int4 hi4 = *reinterpret_cast<const int4 *>(&st_hi[buf][row0]);
-                const int lo_e[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi_e[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+                for (int gg = 0; gg < 4; ++gg) {
+                    const Stats cur = nxt;
+                    if (gg < 3) nxt = read_stats(gg + 1);
+                    KSA_FENCE();
+                    const int lo_e[4] = {cur.lo4.x, cur.lo4.y, cur.lo4.z, cur.lo4.w};
+                    const int span_e[4] = {cur.span4.x, cur.span4.y, cur.span4.z, cur.span4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int g = gg * 4 + e;
-                    const bool vis = key >= lo_e[e] && key < hi_e[e];
-                    const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[g], sl, -l4[e])) : 0.f;
-                    pp[g / 8][g % 8] = (__bf16)p;
-                    pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - d4[e]));
+                    for (int e = 0; e < 4; ++e) {
+                        const int g = gg * 4 + e;
+                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[g], sl, -cur.l4[e]));
+                        // one subtraction and one unsigned compare: lo <= key < lo + span
+                        if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
+                        pp[g / 8][g % 8] = (__bf16)p;
+                        pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - cur.d4[e]));
+                    }
                 }
-            }
+            };
+            if (tile_full)
+                weights(std::false_type{});
+            else
+                weights(std::true_type{});
             KSA_FENCE();
             // ... of its last 16 rows, and the next block's score operands: they land behind the MFMAs below
 #pragma unroll
