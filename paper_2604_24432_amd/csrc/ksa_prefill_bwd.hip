@@ -281,7 +281,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     skip_empty_runs();
     int buf = 0;
     if (seg < item.n_seg) request(seg, kt, 0);
-    int elo[QB], ehi[QB], range_seg = -1;
+    int elo[QB], espan[QB], range_seg = -1, full_lo = 0, full_hi = 0;
     while (seg < item.n_seg) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();   // tile (seg, kt) is complete in buffer buf; everybody is done with the other buffer
@@ -299,10 +299,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
                 int lo, hi;
                 visible_range(a, q_space, idc[qb], space, lo, hi);
                 elo[qb] = lo > seg_begin ? lo : seg_begin;
-                ehi[qb] = hi < seg_end ? hi : seg_end;
-                if (!q_valid[qb]) elo[qb] = 0x7fffffff, ehi[qb] = 0;
+                const int ehi = hi < seg_end ? hi : seg_end;
+                espan[qb] = ehi > elo[qb] ? ehi - elo[qb] : 0;
+                if (!q_valid[qb]) elo[qb] = 0x7fffffff, espan[qb] = 0;
             }
+            full_lo = item.seg[cur_seg].full_lo, full_hi = item.seg[cur_seg].full_hi;
         }
+        const bool tile_full = cur_kt >= full_lo && cur_kt + BN <= full_hi;
         // One 32-key block at a time, both query blocks together: every operand read from LDS feeds QB MFMAs.
         // Source order is the intended issue order, pinned with scheduling fences: every group of LDS reads is issued
         // a whole block of other work ahead of the MFMAs that consume it.
@@ -334,16 +337,26 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
                 for (int db = 0; db < DB; ++db) kt_op[hf][db] = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
             scores_settle();
             // dS^T in the B-operand layout: lane = query, eight registers = eight keys
+            // (a tile the scheduler marks as seen whole by every row of the query tile skips the visibility test)
             bf16x8 pb[QB][2];
+            auto weights = [&](auto masked_tag) {
+                constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
+                for (int qb = 0; qb < QB; ++qb) {
+                    // one subtraction and one unsigned compare per score: elo <= key < elo + espan
+                    const int rel = cur_kt + kb * 32 + 4 * h - elo[qb];
 #pragma unroll
-                for (int g = 0; g < 16; ++g) {
-                    const int key = cur_kt + kb * 32 + 8 * (g / 4) + 4 * h + (g % 4);
-                    const bool vis = key >= elo[qb] && key < ehi[qb];
-                    const float p = vis ? __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -lse2[qb])) : 0.f;
-                    pb[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - dl[qb]));
+                    for (int g = 0; g < 16; ++g) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -lse2[qb]));
+                        if constexpr (MASKED) p = (unsigned)(rel + 8 * (g / 4) + (g % 4)) < (unsigned)espan[qb] ? p : 0.f;
+                        pb[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - dl[qb]));
+                    }
                 }
+            };
+            if (tile_full)
+                weights(std::false_type{});
+            else
+                weights(std::true_type{});
             KSA_FENCE();
             if (kb == 0) {   // the next key block's score operands land behind the MFMAs below
 #pragma unroll
