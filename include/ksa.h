@@ -150,8 +150,8 @@ int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void
 int ksa_prefill_relayout_v(ksa_layout *layout, const void *v, const int64_t kv_strides[3], void *workspace,
                            size_t workspace_bytes, void *stream);
 
-/* Bytes of device scratch memory ksa_prefill_bwd needs for this layout (0 for a NULL layout): one fp32 per
- * (batch, query head, augmented row). */
+/* Bytes of device scratch memory ksa_prefill_bwd needs for this layout (0 for a NULL layout): two fp32 per
+ * (batch, query head, row), the rows of each index space (text, summary) rounded up to a multiple of 64. */
 size_t ksa_prefill_bwd_workspace_bytes(const ksa_layout *layout);
 
 /*

@@ -6,7 +6,7 @@
 //   dS_ij = P_ij (G_i.v_j - delta_i),  delta_i = G_i.O_i  (= sum_l P_il G_i.v_l)
 //   dQ_i  = scale sum_j dS_ij k_j,     dK_j = scale sum_i dS_ij q_i
 // Three kernels, no atomics, results independent of the launch order:
-//   ksa_bwd_delta_kernel  delta_i per (batch, head, row);
+//   ksa_bwd_delta_kernel  delta_i and lse_i log2(e) per (batch, head, row), in compact row order, into the workspace;
 //   ksa_bwd_dq_kernel     one workgroup per query tile of the forward schedule walks that tile's key runs;
 //   ksa_bwd_dkv_kernel    one workgroup per 128-key tile of an index space walks the query rows that can see it
 //                         (two runs, closed form from Eq. 3), for every query head of the KV head's group.
@@ -14,8 +14,10 @@
 // whose registers are the B operand of the next product: dQ works on S^T (keys x queries, the forward kernel's
 // layout, per-lane query statistics), dK/dV on S (queries x keys, per-lane key, per-register query statistics
 // read from LDS).  The operand that has to be contracted over the tile's rows (K^T, Q^T, G^T) is read out of the
-// same row-major LDS tile with the gfx950 transposing read (ds_read_b64_tr_b16).  Every score is masked with its
-// row's visible range (Eq. 3); there is no unmasked fast path yet.
+// same row-major LDS tile with the gfx950 transposing read (ds_read_b64_tr_b16).  The rows a wave owns for the
+// whole kernel (Q and dO, or K and V) and its gradient accumulators live in accumulation registers and feed the
+// MFMAs from there (inline assembly), which leaves the vector registers to the operands streamed through LDS.
+// Tiles that every row sees whole skip the visibility test (Eq. 3); the others clip each score to its row's range.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
