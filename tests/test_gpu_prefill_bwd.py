@@ -94,6 +94,71 @@ def test_small_shapes(case, flags):
     full_compare(cfg, flags)
 
 
+def random_shapes(count, seed):
+    """Seeded draw of small problem shapes: chunk lengths on and off the tile grid, several summaries per chunk or
+    none, windows from 0 to beyond the sequence, text lengths that end inside a chunk, GQA groups 1 to 8."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        c = int(rng.choice([4, 8, 16, 20, 32, 48, 64, 128, 192]))
+        k = int(rng.choice([1, 2, 4, 8]))
+        m = 0 if rng.random() < 0.2 else (c // k if c % k == 0 and c // k <= 16 else 1)
+        if m and c % m:
+            continue
+        C = int(rng.choice([0, 1, 2, 3, 7, 40]))
+        n = int(rng.integers(1, 1100))
+        if rng.random() < 0.5:
+            n = max(c, n // c * c)
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2]))
+        g = int(rng.choice([1, 2, 4, 8]))
+        B = int(rng.choice([1, 2]))
+        out.append((f"r{len(out)}", B, Hkv * g, Hkv, d, n, c, m, C))
+    return out
+
+
+RANDOM = random_shapes(24, seed=20240911)
+
+
+@pytest.mark.parametrize("case", RANDOM, ids=[s[0] for s in RANDOM])
+def test_random_small_shapes(case):
+    name, B, Hq, Hkv, d, n, c, m, C = case
+    cfg = synth.KsaConfig(name, B, Hq, Hkv, d, n, c, m, C, seed=7000 + int(name[1:]))
+    full_compare(cfg, flags=K.KSA_FLAG_SUMMARY_SELF_ONLY if (int(name[1:]) % 4 == 1 and m > 1) else 0)
+
+
+def test_outlier_keys_near_one_hot_rows():
+    """2 % of the K rows multiplied by 8 (the forward's outlier workload): softmax rows dominated by one key.  There
+    dS = P (dP - delta) is a difference of nearly equal numbers, and delta = dO . O carries the bf16 rounding of the
+    forward's output: 2^-9 * |sum_d +-|dO_d O_d|| is about 0.02 for such a row (|O| ~ |v|) and reaches 0.06 in the
+    tail (three sigma of a sum of 128 terms), dS inherits it times P ~ 1, and dQ multiplies it by scale * |k| with
+    |k| up to 8 * 3.5 for an outlier row: 0.088 * 0.06 * 28 = 0.15.  The per-entry bar of dq is therefore 12 times the
+    usual one (8 for the key scale, 1.5 for the tail; measured 0.19), its mean bar 8 times.  dK_j collects the same dS
+    error times scale * |q_i| (0.088 * 0.06 * 3.5 = 0.02) from every row dominated by key j, a handful of them adding
+    up in quadrature: per-entry bar 3 times the usual one (measured 0.028).  dV_j = sum_i P_ij dO_i adds up O(1)
+    terms from the (up to hundreds of) rows dominated by key j, each with the relative error of P, which for these
+    rows is the forward's log-sum-exp error (up to 4e-3 on this workload, see the forward tests): 4e-3 * sqrt(200)
+    = 0.06 without any cancellation in the result: per-entry bar 4 times the usual one (measured 0.059)."""
+    cfg = synth.KsaConfig("outlier_keys", 1, 4, 2, 128, 768, 64, 8, 1, seed=909, key_outlier_frac=0.02)
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    dq, dk, dv = gpu_backward(cfg, q, k, v, g)
+    rq, rk, rv = O.prefill_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.float().numpy(), cfg.n_text,
+                               cfg.chunk_len, cfg.n_summary, cfg.window_chunks)
+    err = np.abs(dq.astype(np.float64) - rq)
+    say(f"  outlier_keys dq: max-abs {err.max():.3e} mean-abs {err.mean():.3e} (largest entry {np.abs(rq).max():.2f})")
+    assert np.isfinite(dq).all()
+    assert (err <= 12 * MAX_ABS + REL * np.abs(rq)).all() and err.mean() <= 8 * MEAN_ABS
+    kerr = np.abs(dk.astype(np.float64) - rk)
+    say(f"  outlier_keys dk: max-abs {kerr.max():.3e} mean-abs {kerr.mean():.3e} (largest entry {np.abs(rk).max():.2f})")
+    assert np.isfinite(dk).all()
+    assert (kerr <= 3 * MAX_ABS + REL * np.abs(rk)).all() and kerr.mean() <= MEAN_ABS
+    verr = np.abs(dv.astype(np.float64) - rv)
+    say(f"  outlier_keys dv: max-abs {verr.max():.3e} mean-abs {verr.mean():.3e} (largest entry {np.abs(rv).max():.2f})")
+    assert np.isfinite(dv).all()
+    assert (verr <= 4 * MAX_ABS + REL * np.abs(rv)).all() and verr.mean() <= MEAN_ABS
+
+
 def test_explicit_scale_and_strided_tensors():
     """Q, K, V cut out of one packed projection output (heads interleaved), an explicit softmax scale."""
     cfg = synth.KsaConfig("packed_qkv", 1, 4, 2, 128, 448, 64, 8, 1, seed=77)
