@@ -81,3 +81,32 @@ def test_cache_entry_points_validate_before_touching_the_gpu():
                                       None) == -3
     assert lib.ksa_decode_summary_fwd(C.byref(p0), vp(a), vp(a), vp(a), vp(a), vp(a), None, None, vp(a), 1 << 20, 1,
                                       None) == -1
+
+
+def test_prefill_bwd_validates_before_touching_the_gpu():
+    """ksa_prefill_bwd: null / misaligned pointers, bad strides and a short workspace are reported by the argument checks,
+    which run before the first HIP call; the workspace is two fp32 per (batch, query head, padded row)."""
+    lib = binding.lib()
+    p = params_for(600, 64, 8, 1, B=2, Hq=4, Hkv=2, d=64)
+    lay = K.ksa_build_layout(p)
+    n_sum = (600 // 64) * 8
+    pad = lambda x: (x + 63) // 64 * 64
+    assert binding.prefill_bwd_workspace_bytes(lay) == 2 * 4 * 2 * 4 * (pad(600) + pad(n_sum))
+    assert lib.ksa_prefill_bwd_workspace_bytes(None) == 0
+    buf = C.create_string_buffer(4096 + 16)
+    a = (C.addressof(buf) + 15) & ~15            # a 16-byte aligned host address: never dereferenced by these checks
+    vp = C.c_void_p
+    big = 1 << 30
+
+    def call(q=a, k=a, v=a, o=a, lse=a, g=a, dq=a, dk=a, dv=a, qs=None, ws=a, ws_bytes=big, layout=lay.handle):
+        return lib.ksa_prefill_bwd(layout, vp(q), vp(k), vp(v), vp(o), vp(lse), vp(g), vp(dq), vp(dk), vp(dv), qs, None,
+                                   None, None, None, vp(ws), ws_bytes, None)
+
+    assert call(layout=None) == -1
+    for name in ("q", "k", "v", "o", "lse", "g", "dq", "dk", "dv", "ws"):
+        assert call(**{name: None}) == -1, name
+    for name in ("q", "k", "v", "o", "g", "dq", "dk", "dv", "ws"):
+        assert call(**{name: a + 2}) == -1, name
+    assert call(lse=a + 2) == -1
+    assert call(qs=(C.c_int64 * 3)(100, 12, 64)) == -1        # row stride not a multiple of 8 elements
+    assert call(ws_bytes=64) == -3
