@@ -44,6 +44,15 @@ __device__ __forceinline__ void lds_direct_load_16(const __bf16 *src, const unsi
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory");
 }
 
+// lds_direct_load_16() with a wave-uniform base address in scalar registers plus a per-lane unsigned byte offset:
+// nothing but the load itself goes through the vector issue port.
+__device__ __forceinline__ void lds_direct_load_16_s(const __bf16 *sbase, unsigned voff_bytes, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff_bytes), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+
 inline int log2_exact(int x) {
     if (x <= 0 || (x & (x - 1))) return -1;
     int s = 0;

@@ -147,15 +147,6 @@ __device__ __forceinline__ void lane_offsets_vt(int vt_stride, int wave, int lan
     }
 }
 
-// lds_direct_load_16() with a wave-uniform base address in scalar registers plus a per-lane unsigned byte offset:
-// nothing but the load itself goes through the vector issue port.
-__device__ __forceinline__ void lds_direct_load_16_s(const __bf16 *sbase, unsigned voff_bytes, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff_bytes), "s"(sbase), "s"(lds_addr)
-                 : "memory");
-}
-
 template <int D>
 __device__ __forceinline__ void issue_tile_load(const __bf16 *gbase, const int (&off)[Tile<D>::NI], unsigned char *lds,
                                                 int buf_off, int wave) {

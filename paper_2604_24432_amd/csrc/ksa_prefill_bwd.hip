@@ -81,6 +81,56 @@ __device__ __forceinline__ void load_tile_pair(const BwdArgs &a, const __bf16 *b
     }
 }
 
+// The same for a tile none of whose rows is clamped, in an index space whose 64-row blocks all start at the same phase
+// of the chunk pattern (64 is a multiple of the period, or the period a multiple of 64): a lane's rows then sit at a
+// fixed distance from the block's first row in every block, so its byte offsets are computed once (tile_offsets) and a
+// request costs the scalar address of the first row plus the loads themselves.
+template <int D>
+struct TileOffsets {
+    static constexpr int NI = RW / (64 / (D / 8));
+    unsigned off0[NI], off1[NI];
+};
+
+__device__ __forceinline__ bool blocks_repeat(int period) { return period > 0 && (BN % period == 0 || period % BN == 0); }
+
+template <int D>
+__device__ __forceinline__ bool tile_offsets(const BwdArgs &a, int space, int64_t row_stride0, int64_t row_stride1, int wave,
+                                             int lane, TileOffsets<D> &t) {
+    constexpr int CH = D / 8, RPI = 64 / CH, NI = TileOffsets<D>::NI;
+    bool fits = true;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int row = RW * wave + RPI * i + lane / CH;
+        const int col = ((lane % CH) ^ swz<D>(row)) << 3;
+        const int64_t rel = aug_row(a, space, row) - aug_row(a, space, 0);
+        const int64_t b0 = (rel * row_stride0 + col) * 2, b1 = (rel * row_stride1 + col) * 2;
+        fits &= b0 < ((int64_t)1 << 31) && b1 < ((int64_t)1 << 31);
+        t.off0[i] = (unsigned)b0, t.off1[i] = (unsigned)b1;
+    }
+    return __builtin_amdgcn_ballot_w64(!fits) == 0;
+}
+
+__device__ __forceinline__ const __bf16 *uniform_ptr(const __bf16 *p) {
+    const uint64_t v = (uint64_t)(size_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const __bf16 *>((size_t)(((uint64_t)hi << 32) | lo));
+}
+
+// row0_* = address of the block's first row (wave-uniform)
+template <int D>
+__device__ __forceinline__ void load_tile_pair_fast(const __bf16 *row0_0, const __bf16 *row0_1, const TileOffsets<D> &t,
+                                                    const unsigned char *tile0, const unsigned char *tile1, int wave) {
+    constexpr int RPI = 64 / (D / 8), NI = TileOffsets<D>::NI;
+    const __bf16 *s0 = uniform_ptr(row0_0), *s1 = uniform_ptr(row0_1);
+    const unsigned l0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)tile0) + RW * wave * (D * 2);
+    const unsigned l1 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)tile1) + RW * wave * (D * 2);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        lds_direct_load_16_s(s0, t.off0[i], l0 + RPI * i * (D * 2));
+        lds_direct_load_16_s(s1, t.off1[i], l1 + RPI * i * (D * 2));
+    }
+}
+
 // global -> LDS, 4 bytes per lane: the wave's 64 pieces land back to back (lane order) from the wave-uniform LDS
 // address dst.  Inline assembly for the same reason as lds_direct_load_16().
 __device__ __forceinline__ void lds_direct_load_4(const float *src, const unsigned char *dst) {
@@ -405,7 +455,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[STAGES * 2 * BYTES];
     __shared__ __attribute__((aligned(256))) float st_lse[STAGES][BN], st_dl[STAGES][BN];
     __shared__ __attribute__((aligned(16))) int st_lo[STAGES][BN], st_span[STAGES][BN];   // visible keys: [lo, lo + span)
-    __shared__ int st_full[STAGES];   // 1: every row of the tile sees every key of the workgroup
 
     // Workgroup index -> (key tile, batch, KV head), the head running fastest: consecutive workgroup ids go to the
     // XCDs round-robin, so with 8 (batch, KV head) pairs all key tiles of a head share one L2, and they walk the same
@@ -483,26 +532,48 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // below can count them.
     constexpr int LOADS_PER_TILE = 2 * (RW / (64 / (D / 8))) + 2;
     const int stats_stride = a.nt_pad + a.ns_pad;
+    TileOffsets<D> toff[2];
+    bool fast[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+        fast[x] = blocks_repeat(run_space[x] == KSA_SPACE_TEXT ? a.c : a.m) &&
+                  tile_offsets<D>(a, run_space[x], a.qs[1], a.os[1], wave, lane, toff[x]);
+    unsigned full_mask = 0;   // bit `stage`: every row of the tile in that stage sees every key of the workgroup
     auto request = [&](int stage) {
         const int head = hkv * a.group + hj, q_space = run_space[run];
         const int first = (run_first_blk[run] + run_tiles[run] - 1 - ti) * BN;
         const __bf16 *qbase = a.q + b * a.qs[0] + head * a.qs[2];
         const __bf16 *gbase = a.g + b * a.os[0] + head * a.os[2];
-        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, lds + stage * 2 * BYTES,
-                          lds + stage * 2 * BYTES + BYTES, wave, lane);
+        unsigned char *q_tile = lds + stage * 2 * BYTES, *g_tile = q_tile + BYTES;
+        const bool whole = first >= run_begin[run] && first + BN <= run_end[run];   // no row of the block outside the run
+        if (fast[run] && first + BN <= run_end[run]) {
+            const int64_t row0 = aug_row(a, q_space, first);
+            load_tile_pair_fast<D>(qbase + row0 * a.qs[1], gbase + row0 * a.os[1], toff[run], q_tile, g_tile, wave);
+        } else {
+            load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, q_tile, g_tile, wave, lane);
+        }
         // lse and delta of the 64 rows: one 4-byte piece per lane, straight into LDS (all waves fetch the same 256
         // bytes: keeps the per-wave load count uniform, and costs nothing)
         const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (q_space == KSA_SPACE_TEXT ? 0 : a.nt_pad) +
                            first + lane;
         lds_direct_load_4(a.lse2c + at, reinterpret_cast<const unsigned char *>(&st_lse[stage][0]));
         lds_direct_load_4(a.dlc + at, reinterpret_cast<const unsigned char *>(&st_dl[stage][0]));
-        if (tid < BN) {   // visible key range of each row (empty for rows of the block outside the run)
+        // Visible ranges are monotone in the row index (Eq. 3: both ends of a row's range never move backwards from one
+        // row to the next), so the block is seen whole iff its last row's range starts at or before the first key and
+        // its first row's range ends at or behind the last key: two scalar evaluations, no per-row work.
+        bool full = false;
+        if (whole) {
+            int lo_f, hi_f, lo_l, hi_l;
+            visible_range(a, q_space, first, space, lo_f, hi_f);
+            visible_range(a, q_space, first + BN - 1, space, lo_l, hi_l);
+            full = lo_l <= k0 && hi_f >= k1;
+        }
+        full_mask = (full_mask & ~(1u << stage)) | ((full ? 1u : 0u) << stage);
+        if (!full && tid < BN) {   // visible key range of each row (empty for rows of the block outside the run)
             const int qi = first + tid;
             int lo = 0x7fffffff, hi = 0;
             if (qi >= run_begin[run] && qi < run_end[run]) visible_range(a, q_space, qi, space, lo, hi);
             st_lo[stage][tid] = lo, st_span[stage][tid] = hi > lo ? hi - lo : 0;
-            const bool sees_all = lo <= k0 && hi >= k1;
-            if (tid == 0) st_full[stage] = __builtin_amdgcn_ballot_w64(sees_all) == ~0ull ? 1 : 0;
         }
         if (++hj == a.group) hj = 0, ++ti;
         skip_empty_runs();
@@ -526,7 +597,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
             --pending;
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
-        const bool tile_full = __builtin_amdgcn_readfirstlane(st_full[buf]) != 0;
+        const bool tile_full = ((full_mask >> buf) & 1u) != 0;
         // Source order below is the intended issue order, pinned with scheduling fences: every group of LDS reads is
         // issued a whole block of other work ahead of the MFMAs that consume it (one wave per SIMD has nobody else
         // to hide the LDS latency behind; left alone, the compiler puts each read right in front of its MFMA).
