@@ -333,8 +333,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     skip_empty_runs();
     int buf = 0;
     if (seg < item.n_seg) request(seg, kt, 0);
-    int elo[QB], espan[QB], range_seg = -1, full_lo = 0, full_hi = 0;
-    while (seg < item.n_seg) {
+    int elo[QB], espan[QB], range_seg = -1;
+    // One tile: publish it, request the next one, compute.  MASKED tiles clip every score to its row's visible range;
+    // tiles the schedule marks as seen whole by every row of the query tile do not.  The two variants are separate
+    // instantiations walked in stretches (as in the forward kernel), so that the loop body carries no branch.
+    auto step = [&](auto masked_tag) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();   // tile (seg, kt) is complete in buffer buf; everybody is done with the other buffer
         const int cur_seg = seg, cur_kt = kt;
@@ -355,74 +358,111 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
                 espan[qb] = ehi > elo[qb] ? ehi - elo[qb] : 0;
                 if (!q_valid[qb]) elo[qb] = 0x7fffffff, espan[qb] = 0;
             }
-            full_lo = item.seg[cur_seg].full_lo, full_hi = item.seg[cur_seg].full_hi;
         }
-        const bool tile_full = cur_kt >= full_lo && cur_kt + BN <= full_hi;
-        // One 32-key block at a time, both query blocks together: every operand read from LDS feeds QB MFMAs.
-        // Source order is the intended issue order, pinned with scheduling fences: every group of LDS reads is issued
-        // a whole block of other work ahead of the MFMAs that consume it.
-        bf16x8 ka[KS], va[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 0, s), va[s] = read_rows<D>(lds, v_rows, 0, s);
-        KSA_FENCE();
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            f32x16 sacc[QB], gacc[QB];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                mfma_score<true>(sacc[qb], ka[0], qreg[qb][0]);
-                mfma_score<true>(gacc[qb], va[0], greg[qb][0]);
-            }
-#pragma unroll
-            for (int s = 1; s < KS; ++s)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    mfma_score<false>(sacc[qb], ka[s], qreg[qb][s]);
-                    mfma_score<false>(gacc[qb], va[s], greg[qb][s]);
-                }
-            KSA_FENCE();
-            // K^T operands of this key block: they land while the VALU block below runs
-            bf16x8 kt_op[2][DB];
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                for (int db = 0; db < DB; ++db) kt_op[hf][db] = read_cols<D>(lds, k_cols, kb * 32 + hf * 16, db);
-            scores_settle();
-            // dS^T in the B-operand layout: lane = query, eight registers = eight keys
-            // (a tile the scheduler marks as seen whole by every row of the query tile skips the visibility test)
-            bf16x8 pb[QB][2];
-            auto weights = [&](auto masked_tag) {
+            // The tile's two 32-key blocks are two streams, each scores -> weights -> dQ, both query blocks of the wave
+            // together (every operand read from LDS feeds QB MFMAs).  One wave per SIMD has nobody else to fill the
+            // matrix pipe while its VALU block runs, so the streams are interleaved by hand: the weights of block 0 are
+            // computed in eight chunks with the score MFMAs of block 1 dealt between them, the weights of block 1 with
+            // the dQ MFMAs of block 0.  Source order is the intended issue order, pinned with scheduling fences; LDS
+            // operands are read one step ahead of the MFMAs that consume them.
+            constexpr int NC = 8;   // chunks of the VALU block: two scores per query block each
+            f32x16 sacc[2][QB], gacc[2][QB];
+            bf16x8 pb[2][QB][2];    // dS^T in the B-operand layout: lane = query, eight registers = eight keys
+            auto weights_chunk = [&](auto masked_tag, int kb, int c) {
                 constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
                     // one subtraction and one unsigned compare per score: elo <= key < elo + espan
                     const int rel = cur_kt + kb * 32 + 4 * h - elo[qb];
 #pragma unroll
-                    for (int g = 0; g < 16; ++g) {
-                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -lse2[qb]));
+                    for (int g = 2 * c; g < 2 * c + 2; ++g) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][g], sl, -lse2[qb]));
                         if constexpr (MASKED) p = (unsigned)(rel + 8 * (g / 4) + (g % 4)) < (unsigned)espan[qb] ? p : 0.f;
-                        pb[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - dl[qb]));
+                        pb[kb][qb][g / 8][g % 8] = (__bf16)(p * (gacc[kb][qb][g] - dl[qb]));
                     }
                 }
             };
-            if (tile_full)
-                weights(std::false_type{});
-            else
-                weights(std::true_type{});
-            KSA_FENCE();
-            if (kb == 0) {   // the next key block's score operands land behind the MFMAs below
+            auto weights = [&](int kb, int c) { weights_chunk(masked_tag, kb, c); };
+            auto score_step = [&](int kb, int s, const bf16x8 &k_op, const bf16x8 &v_op) {
 #pragma unroll
-                for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 1, s), va[s] = read_rows<D>(lds, v_rows, 1, s);
+                for (int qb = 0; qb < QB; ++qb) {
+                    if (s == 0) {
+                        mfma_score<true>(sacc[kb][qb], k_op, qreg[qb][0]);
+                        mfma_score<true>(gacc[kb][qb], v_op, greg[qb][0]);
+                    } else {
+                        mfma_score<false>(sacc[kb][qb], k_op, qreg[qb][s]);
+                        mfma_score<false>(gacc[kb][qb], v_op, greg[qb][s]);
+                    }
+                }
+            };
+            // dQ^T += K^T dS^T for the pair j = (16-key group hf, 32-column block db) of key block kb
+            auto dq_step = [&](int kb, int j, const bf16x8 &kt_op) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][j % DB], kt_op, pb[kb][qb][j / DB]);
+            };
+
+            // ---- scores of block 0 (alone on the matrix pipe)
+            {
+                bf16x8 ka[KS], va[KS];
+#pragma unroll
+                for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 0, s), va[s] = read_rows<D>(lds, v_rows, 0, s);
+                KSA_FENCE();
+#pragma unroll
+                for (int s = 0; s < KS; ++s) score_step(0, s, ka[s], va[s]);
+                KSA_FENCE();
             }
+            // ---- weights of block 0 between the scores of block 1
+            {
+                bf16x8 ka[KS], va[KS];
+                ka[0] = read_rows<D>(lds, k_rows, 1, 0), va[0] = read_rows<D>(lds, v_rows, 1, 0);
+                scores_settle();
+                KSA_FENCE();
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if ((c * KS) % NC == 0) {
+                        const int s = c * KS / NC;
+                        if (s + 1 < KS) ka[s + 1] = read_rows<D>(lds, k_rows, 1, s + 1), va[s + 1] = read_rows<D>(lds, v_rows, 1, s + 1);
+                        score_step(1, s, ka[s], va[s]);
+                    }
+                    weights(0, c);
+                    KSA_FENCE();
+                }
+            }
+            // ---- weights of block 1 between the dQ products of block 0
+            bf16x8 kt1[2 * DB];
+            {
+                bf16x8 kt0[2 * DB];
+                kt0[0] = read_cols<D>(lds, k_cols, 0, 0);
+                scores_settle();
+                KSA_FENCE();
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    if ((c * 2 * DB) % NC == 0) {
+                        const int j = c * 2 * DB / NC;
+                        if (j + 1 < 2 * DB) kt0[j + 1] = read_cols<D>(lds, k_cols, ((j + 1) / DB) * 16, (j + 1) % DB);
+                        dq_step(0, j, kt0[j]);
+                    }
+                    weights(1, c);
+                    if (c == NC - 1) {
+#pragma unroll
+                        for (int j = 0; j < 2 * DB; ++j) kt1[j] = read_cols<D>(lds, k_cols, 32 + (j / DB) * 16, j % DB);
+                    }
+                    KSA_FENCE();
+                }
+            }
+            // ---- dQ products of block 1 (alone on the matrix pipe)
+#pragma unroll
+            for (int j = 0; j < 2 * DB; ++j) dq_step(1, j, kt1[j]);
             KSA_FENCE();
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][db], kt_op[hf][db], pb[qb][hf]);
-            KSA_FENCE();
+    };
+    auto tile_is_full = [&]() { return kt >= item.seg[seg].full_lo && kt + BN <= item.seg[seg].full_hi; };
+    while (seg < item.n_seg) {
+        if (tile_is_full()) {
+            do step(std::false_type{});
+            while (seg < item.n_seg && tile_is_full());
+        } else {
+            do step(std::true_type{});
+            while (seg < item.n_seg && !tile_is_full());
         }
     }
 
