@@ -622,7 +622,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     int pending = 0;   // tiles requested and not yet consumed
     for (; pending < STAGES - 1 && run < 2; ++pending) request(pending);
     int buf = 0;       // stage of the oldest pending tile
-    while (pending > 0) {
+    // One tile: publish it, request the tile STAGES - 1 ahead, compute.  The tile's two 32-row blocks are two streams,
+    // each scores -> weights -> gradients, interleaved by hand (one wave per SIMD has nobody else to fill the matrix
+    // pipe while its VALU block runs): the weights of block 0 are computed in four chunks with the score MFMAs of
+    // block 1 dealt between them, the weights of block 1 with the gradient MFMAs of block 0.  Source order is the
+    // intended issue order, pinned with scheduling fences; LDS operands and row statistics are read one step ahead of
+    // their use.  A tile all of whose rows see all of the workgroup's keys (nearly every tile of a summary key) skips
+    // the visibility test: the two variants are separate instantiations walked in stretches.
+    auto step = [&](auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         // the oldest pending tile is complete when at most the loads of the younger ones are outstanding
         if (pending >= 3)
             __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LOADS_PER_TILE) & 15) | (((2 * LOADS_PER_TILE) >> 4) << 14));
@@ -637,98 +645,129 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
             --pending;
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
-        const bool tile_full = ((full_mask >> buf) & 1u) != 0;
-        // Source order below is the intended issue order, pinned with scheduling fences: every group of LDS reads is
-        // issued a whole block of other work ahead of the MFMAs that consume it (one wave per SIMD has nobody else
-        // to hide the LDS latency behind; left alone, the compiler puts each read right in front of its MFMA).
-        bf16x8 qa[KS], ga[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 0, s), ga[s] = read_rows<D>(lds, g_rows, 0, s);
-        KSA_FENCE();
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            f32x16 sacc, gacc;
-            mfma_score<true>(sacc, qa[0], kreg[0]);
-            mfma_score<true>(gacc, ga[0], vreg[0]);
-#pragma unroll
-            for (int s = 1; s < KS; ++s) {
-                mfma_score<false>(sacc, qa[s], kreg[s]);
-                mfma_score<false>(gacc, ga[s], vreg[s]);
+        constexpr int NC = 4;               // chunks of a block's VALU work: four query rows per lane each
+        constexpr int SPC = KS / NC;        // score k steps dealt into one chunk
+        constexpr int PPC = 2 * DB / NC;    // gradient (16-row group, 32-column block) pairs dealt into one chunk
+        static_assert(KS % NC == 0 && (2 * DB) % NC == 0, "the MFMAs of a block are dealt evenly over the chunks");
+        f32x16 sacc[2], gacc[2];
+        bf16x8 pp[2][2], pd[2][2];          // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
+
+        struct Stats { f32x4 l4, d4; int4 lo4, span4; };
+        auto read_stats = [&](int qb, int gg) {
+            const int row0 = qb * 32 + 8 * gg + 4 * h;
+            Stats st;
+            st.l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
+            st.d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
+            if constexpr (MASKED) {
+                st.lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
+                st.span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
             }
+            return st;
+        };
+        auto weights_chunk = [&](int qb, int gg, const Stats &cur) {
+            const int lo_e[4] = {cur.lo4.x, cur.lo4.y, cur.lo4.z, cur.lo4.w};
+            const int span_e[4] = {cur.span4.x, cur.span4.y, cur.span4.z, cur.span4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int g = gg * 4 + e;
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -cur.l4[e]));
+                // one subtraction and one unsigned compare: lo <= key < lo + span
+                if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
+                pp[qb][g / 8][g % 8] = (__bf16)p;
+                pd[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - cur.d4[e]));
+            }
+        };
+        auto score_step = [&](int qb, int s, const bf16x8 &q_op, const bf16x8 &g_op) {
+            if (s == 0) {
+                mfma_score<true>(sacc[qb], q_op, kreg[0]);
+                mfma_score<true>(gacc[qb], g_op, vreg[0]);
+            } else {
+                mfma_score<false>(sacc[qb], q_op, kreg[s]);
+                mfma_score<false>(gacc[qb], g_op, vreg[s]);
+            }
+        };
+        // dV^T += G^T P, dK^T += Q^T dS for the pair j = (16-row group hf, 32-column block db) of query block qb
+        auto grad_step = [&](int qb, int j, const bf16x8 &gt_op, const bf16x8 &qt_op) {
+            mfma_acc(dvacc[j % DB], gt_op, pp[qb][j / DB]);
+            mfma_acc(dkacc[j % DB], qt_op, pd[qb][j / DB]);
+        };
+        auto read_pair = [&](int qb, int j, bf16x8 &gt_op, bf16x8 &qt_op) {
+            gt_op = read_cols<D>(lds, g_cols, qb * 32 + (j / DB) * 16, j % DB);
+            qt_op = read_cols<D>(lds, q_cols, qb * 32 + (j / DB) * 16, j % DB);
+        };
+
+        // ---- scores of block 0 (alone on the matrix pipe)
+        {
+            bf16x8 qa[KS], ga[KS];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 0, s), ga[s] = read_rows<D>(lds, g_rows, 0, s);
             KSA_FENCE();
-            // transposed operands of the block's first 16 rows: they land while the VALU block below runs
-            bf16x8 gt[2][DB], qt[2][DB];
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                gt[0][db] = read_cols<D>(lds, g_cols, qb * 32, db);
-                qt[0][db] = read_cols<D>(lds, q_cols, qb * 32, db);
-            }
+            for (int s = 0; s < KS; ++s) score_step(0, s, qa[s], ga[s]);
+            KSA_FENCE();
+        }
+        // ---- weights of block 0 between the scores of block 1
+        {
+            bf16x8 qa[KS], ga[KS];
+            qa[0] = read_rows<D>(lds, q_rows, 1, 0), ga[0] = read_rows<D>(lds, g_rows, 1, 0);
+            Stats nxt = read_stats(0, 0);
             scores_settle();
-            // P and dS in the B-operand layout: lane = key, eight registers = eight query rows.  The statistics of the
-            // next four rows are read while the current four are worked on; a tile all of whose rows see all of the
-            // workgroup's keys (nearly every tile of a summary key) skips the visibility test.
-            bf16x8 pp[2], pd[2];
-            auto weights = [&](auto masked_tag) {
-                constexpr bool MASKED = decltype(masked_tag)::value;
-                struct Stats { f32x4 l4, d4; int4 lo4, span4; };
-                auto read_stats = [&](int gg) {
-                    const int row0 = qb * 32 + 8 * gg + 4 * h;
-                    Stats st;
-                    st.l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
-                    st.d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
-                    if constexpr (MASKED) {
-                        st.lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
-                        st.span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
-                    }
-                    return st;
-                };
-                Stats nxt = read_stats(0);
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    const Stats cur = nxt;
-                    if (gg < 3) nxt = read_stats(gg + 1);
-                    KSA_FENCE();
-                    const int lo_e[4] = {cur.lo4.x, cur.lo4.y, cur.lo4.z, cur.lo4.w};
-                    const int span_e[4] = {cur.span4.x, cur.span4.y, cur.span4.z, cur.span4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int g = gg * 4 + e;
-                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[g], sl, -cur.l4[e]));
-                        // one subtraction and one unsigned compare: lo <= key < lo + span
-                        if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
-                        pp[g / 8][g % 8] = (__bf16)p;
-                        pd[g / 8][g % 8] = (__bf16)(p * (gacc[g] - cur.d4[e]));
-                    }
-                }
-            };
-            if (tile_full)
-                weights(std::false_type{});
-            else
-                weights(std::true_type{});
             KSA_FENCE();
-            // ... of its last 16 rows, and the next block's score operands: they land behind the MFMAs below
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                gt[1][db] = read_cols<D>(lds, g_cols, qb * 32 + 16, db);
-                qt[1][db] = read_cols<D>(lds, q_cols, qb * 32 + 16, db);
-            }
-            if (qb == 0) {
+            for (int gg = 0; gg < NC; ++gg) {
+                const Stats cur = nxt;
+                if (gg + 1 < NC) nxt = read_stats(0, gg + 1);
 #pragma unroll
-                for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 1, s), ga[s] = read_rows<D>(lds, g_rows, 1, s);
-            }
-            KSA_FENCE();
-            // dV^T += G^T P,  dK^T += Q^T dS
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    mfma_acc(dvacc[db], gt[hf][db], pp[hf]);
-                    mfma_acc(dkacc[db], qt[hf][db], pd[hf]);
+                for (int x = 0; x < SPC; ++x) {
+                    const int s = gg * SPC + x;
+                    if (s + 1 < KS) qa[s + 1] = read_rows<D>(lds, q_rows, 1, s + 1), ga[s + 1] = read_rows<D>(lds, g_rows, 1, s + 1);
+                    score_step(1, s, qa[s], ga[s]);
                 }
+                weights_chunk(0, gg, cur);
                 KSA_FENCE();
             }
         }
+        // ---- weights of block 1 between the gradient products of block 0
+        bf16x8 gt1[2 * DB], qt1[2 * DB];
+        {
+            bf16x8 gt0[2 * DB], qt0[2 * DB];
+            read_pair(0, 0, gt0[0], qt0[0]);
+            Stats nxt = read_stats(1, 0);
+            scores_settle();
+            KSA_FENCE();
+#pragma unroll
+            for (int gg = 0; gg < NC; ++gg) {
+                const Stats cur = nxt;
+                if (gg + 1 < NC) nxt = read_stats(1, gg + 1);
+#pragma unroll
+                for (int x = 0; x < PPC; ++x) {
+                    const int j = gg * PPC + x;
+                    if (j + 1 < 2 * DB) read_pair(0, j + 1, gt0[j + 1], qt0[j + 1]);
+                    grad_step(0, j, gt0[j], qt0[j]);
+                }
+                weights_chunk(1, gg, cur);
+                if (gg == NC - 1) read_pair(1, 0, gt1[0], qt1[0]);
+                KSA_FENCE();
+            }
+        }
+        // ---- gradient products of block 1 (alone on the matrix pipe)
+#pragma unroll
+        for (int j = 0; j < 2 * DB; ++j) {
+            if (j + 1 < 2 * DB) read_pair(1, j + 1, gt1[j + 1], qt1[j + 1]);
+            grad_step(1, j, gt1[j], qt1[j]);
+        }
+        KSA_FENCE();
         buf = (buf + 1) % STAGES;
+    };
+    auto next_is_full = [&]() { return ((full_mask >> buf) & 1u) != 0; };
+    while (pending > 0) {
+        if (next_is_full()) {
+            do step(std::false_type{});
+            while (pending > 0 && next_is_full());
+        } else {
+            do step(std::true_type{});
+            while (pending > 0 && !next_is_full());
+        }
     }
 
     accumulators_settle();
