@@ -81,56 +81,6 @@ __device__ __forceinline__ void load_tile_pair(const BwdArgs &a, const __bf16 *b
     }
 }
 
-// The same for a tile none of whose rows is clamped, in an index space whose 64-row blocks all start at the same phase
-// of the chunk pattern (64 is a multiple of the period, or the period a multiple of 64): a lane's rows then sit at a
-// fixed distance from the block's first row in every block, so its byte offsets are computed once (tile_offsets) and a
-// request costs the scalar address of the first row plus the loads themselves.
-template <int D>
-struct TileOffsets {
-    static constexpr int NI = RW / (64 / (D / 8));
-    unsigned off0[NI], off1[NI];
-};
-
-__device__ __forceinline__ bool blocks_repeat(int period) { return period > 0 && (BN % period == 0 || period % BN == 0); }
-
-template <int D>
-__device__ __forceinline__ bool tile_offsets(const BwdArgs &a, int space, int64_t row_stride0, int64_t row_stride1, int wave,
-                                             int lane, TileOffsets<D> &t) {
-    constexpr int CH = D / 8, RPI = 64 / CH, NI = TileOffsets<D>::NI;
-    bool fits = true;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int row = RW * wave + RPI * i + lane / CH;
-        const int col = ((lane % CH) ^ swz<D>(row)) << 3;
-        const int64_t rel = aug_row(a, space, row) - aug_row(a, space, 0);
-        const int64_t b0 = (rel * row_stride0 + col) * 2, b1 = (rel * row_stride1 + col) * 2;
-        fits &= b0 < ((int64_t)1 << 31) && b1 < ((int64_t)1 << 31);
-        t.off0[i] = (unsigned)b0, t.off1[i] = (unsigned)b1;
-    }
-    return __builtin_amdgcn_ballot_w64(!fits) == 0;
-}
-
-__device__ __forceinline__ const __bf16 *uniform_ptr(const __bf16 *p) {
-    const uint64_t v = (uint64_t)(size_t)p;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const __bf16 *>((size_t)(((uint64_t)hi << 32) | lo));
-}
-
-// row0_* = address of the block's first row (wave-uniform)
-template <int D>
-__device__ __forceinline__ void load_tile_pair_fast(const __bf16 *row0_0, const __bf16 *row0_1, const TileOffsets<D> &t,
-                                                    const unsigned char *tile0, const unsigned char *tile1, int wave) {
-    constexpr int RPI = 64 / (D / 8), NI = TileOffsets<D>::NI;
-    const __bf16 *s0 = uniform_ptr(row0_0), *s1 = uniform_ptr(row0_1);
-    const unsigned l0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)tile0) + RW * wave * (D * 2);
-    const unsigned l1 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)tile1) + RW * wave * (D * 2);
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        lds_direct_load_16_s(s0, t.off0[i], l0 + RPI * i * (D * 2));
-        lds_direct_load_16_s(s1, t.off1[i], l1 + RPI * i * (D * 2));
-    }
-}
-
 // global -> LDS, 4 bytes per lane: the wave's 64 pieces land back to back (lane order) from the wave-uniform LDS
 // address dst.  Inline assembly for the same reason as lds_direct_load_16().
 __device__ __forceinline__ void lds_direct_load_4(const float *src, const unsigned char *dst) {
@@ -572,12 +522,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // below can count them.
     constexpr int LOADS_PER_TILE = 2 * (RW / (64 / (D / 8))) + 2;
     const int stats_stride = a.nt_pad + a.ns_pad;
-    TileOffsets<D> toff[2];
-    bool fast[2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-        fast[x] = blocks_repeat(run_space[x] == KSA_SPACE_TEXT ? a.c : a.m) &&
-                  tile_offsets<D>(a, run_space[x], a.qs[1], a.os[1], wave, lane, toff[x]);
     unsigned full_mask = 0;   // bit `stage`: every row of the tile in that stage sees every key of the workgroup
     auto request = [&](int stage) {
         const int head = hkv * a.group + hj, q_space = run_space[run];
@@ -586,12 +530,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
         const __bf16 *gbase = a.g + b * a.os[0] + head * a.os[2];
         unsigned char *q_tile = lds + stage * 2 * BYTES, *g_tile = q_tile + BYTES;
         const bool whole = first >= run_begin[run] && first + BN <= run_end[run];   // no row of the block outside the run
-        if (fast[run] && first + BN <= run_end[run]) {
-            const int64_t row0 = aug_row(a, q_space, first);
-            load_tile_pair_fast<D>(qbase + row0 * a.qs[1], gbase + row0 * a.os[1], toff[run], q_tile, g_tile, wave);
-        } else {
-            load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, q_tile, g_tile, wave, lane);
-        }
+        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, q_tile, g_tile, wave, lane);
         // lse and delta of the 64 rows: one 4-byte piece per lane, straight into LDS (all waves fetch the same 256
         // bytes: keeps the per-wave load count uniform, and costs nothing)
         const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (q_space == KSA_SPACE_TEXT ? 0 : a.nt_pad) +
