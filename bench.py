@@ -233,6 +233,23 @@ def prefill_backward(cfg, lay, q, k, v, o, lse, steps):
             "kernels": "ksa_bwd_delta_kernel, ksa_bwd_dq_kernel, ksa_bwd_dkv_kernel (split in profiles/)"}
 
 
+def backward_of(lay, q, k, v, o, lse, seed, calls=2):
+    """ms per ksa_prefill_bwd call for tensors already on the GPU (N(0,1) upstream gradient drawn here)."""
+    import torch
+    import paper_2604_24432_amd as K
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    g = torch.randn(o.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(K.prefill_bwd_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+
+    def bwd():
+        K.ksa_prefill_bwd(lay, q, k, v, o, lse, g, dq=dq, dk=dk, dv=dv, workspace=ws)
+
+    bwd()
+    return float(np.mean(time_events(bwd, calls)))
+
+
 def full_attention_reference(cfg, q, k, v, ksa_ms):
     """Not part of the timed step: dense causal attention over the same number of text tokens through the same
     library (no summaries, every earlier chunk in the window), i.e. what the summary mask saves at this length."""
@@ -249,10 +266,13 @@ def full_attention_reference(cfg, q, k, v, ksa_ms):
     K.ksa_prefill_fwd(lay, qd, kd, vd, o=od, lse=ld, workspace=ws)
     ms = float(np.mean(time_events(lambda: K.ksa_prefill_fwd(lay, qd, kd, vd, o=od, lse=ld, workspace=ws), 3)))
     flops = 4.0 * cfg.head_dim * cfg.batch * cfg.n_q_heads * live_pairs(n, c, 0, n // c)
+    bwd_ms = backward_of(lay, qd, kd, vd, od, ld, cfg.seed + 60, calls=1)
     return {"workload": f"dense causal, B{cfg.batch} Hq{cfg.n_q_heads} Hkv{cfg.n_kv_heads} d{cfg.head_dim} n{n}",
             "ms": round(ms, 3), "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "ksa_prefill_speedup": round(ms / ksa_ms, 2)}
+            "ksa_prefill_speedup": round(ms / ksa_ms, 2),
+            "backward_ms": round(bwd_ms, 2),
+            "backward_frac_mfma_peak": round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
 def paper_shape_reference(cfg):
@@ -274,9 +294,12 @@ def paper_shape_reference(cfg):
     K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws)
     ms = float(np.mean(time_events(lambda: K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws), 5)))
     flops = 4.0 * pc.head_dim * pc.batch * pc.n_q_heads * live_pairs(pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks)
+    bwd_ms = backward_of(lay, q, k, v, o, lse, pc.seed + 7)
     return {"workload": f"B{pc.batch} Hq{pc.n_q_heads} Hkv{pc.n_kv_heads} d{pc.head_dim} n{pc.n_text} c8 m1 C128, L={pc.aug_len}",
             "ms": round(ms, 3), "live_flops": flops, "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
-            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "backward_ms": round(bwd_ms, 2),
+            "backward_frac_mfma_peak": round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
 def cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args):
