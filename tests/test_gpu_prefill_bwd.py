@@ -238,3 +238,14 @@ def test_bench_shape_128k_sampled_rows():
              [aug_summary(cfg, n_sum - 1 - int(x)) for x in rng.integers(0, 4 * cfg.n_summary, 2)] + \
              [aug_summary(cfg, n_sum - 3 * cfg.n_summary)]
     sampled_compare(cfg, q_rows, sorted(set(k_rows)), cfg.name)
+
+
+def test_prefill_4k_sampled_rows():
+    """The 4K workload (two sequences, 32 query / 8 KV heads): random query rows and key rows of both kinds."""
+    cfg = synth.CONFIGS["prefill_4k"]
+    rng = np.random.default_rng(2100)
+    n_sum = (cfg.n_text // cfg.chunk_len) * cfg.n_summary
+    q_rows = sorted(set([0, cfg.aug_len - 1] + [int(x) for x in rng.integers(0, cfg.aug_len, 14)]))
+    k_rows = sorted(set([aug_text(cfg, int(x)) for x in rng.integers(0, cfg.n_text, 5)] +
+                        [aug_summary(cfg, int(x)) for x in rng.integers(0, n_sum, 5)] + [aug_summary(cfg, 0)]))
+    sampled_compare(cfg, q_rows, k_rows, cfg.name)
