@@ -182,6 +182,31 @@ def test_softmax_invariants():
             assert abs(math.exp(lse[0, h, a]) - len(cols)) < 1e-9
 
 
+def test_row_weights_values_with_grouped_heads():
+    """Value pin of row_weights: for several (b, h, aq) with Hq != Hkv and B > 1 the weights, applied to the V rows
+    of the query head's KV head, must reproduce the prefill row, the log-sum-exp must agree, and each weight must
+    equal exp(scale * q.k - lse) written out here.  A wrong batch / KV-head / row offset in the wrapper fails all
+    three (every batch and every KV head holds different random data)."""
+    n, c, m, Cw = 48, 8, 2, 1
+    L = O.aug_len(n, c, m)
+    B, Hq, Hkv, d = 2, 6, 2, 16
+    q, k, v = rand_qkv(B, L, Hq, Hkv, d, seed=21)
+    scale = 0.3
+    o, lse = O.prefill(q, k, v, n=n, c=c, m=m, Cw=Cw, scale=scale)
+    M = O.mask(n, c, m, Cw)
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // (Hq // Hkv)
+            for a in [0, 9, 10, 27, 31, L - 11, L - 1]:
+                w, l = O.row_weights(q, k, n, c, m, Cw, b, h, a, scale=scale)
+                assert abs(l - lse[b, h, a]) < 1e-13
+                got = w @ v[b, :, hk, :].astype(np.float64)
+                assert np.abs(got - o[b, a, h]).max() < 1e-13
+                s = scale * (k[b, :, hk, :].astype(np.float64) @ q[b, a, h].astype(np.float64))
+                want = np.where(M[a] == 1, np.exp(s - l), 0.0)
+                assert np.abs(w - want).max() < 1e-13
+
+
 def test_scale_default_and_shift_invariance():
     n, c, m, Cw = 32, 8, 1, 1
     L = O.aug_len(n, c, m)
