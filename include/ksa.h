@@ -87,9 +87,10 @@ int ksa_layout_upload(ksa_layout *layout);
 /* ---- introspection (host arrays, caller-allocated) used by the bit-exact layout tests ---------- */
 
 /* L = (n/c) * (c+m) + n mod c augmented rows (an incomplete last chunk has text rows only), J = n/c whole chunks,
- * and the query / key tile heights of the schedule. */
+ * the query / key tile heights of the schedule, and the number of query heads (of one KV head) a prefill
+ * workgroup handles together: 1, 2 or 4, with q_tile_rows * heads_per_workgroup = 256.  Any pointer may be NULL. */
 int ksa_layout_dims(const ksa_layout *layout, int64_t *aug_len, int32_t *n_chunks, int32_t *q_tile_rows,
-                    int32_t *k_tile_rows);
+                    int32_t *k_tile_rows, int32_t *heads_per_workgroup);
 /* Eq. 1 index maps.  aug_chunk, aug_is_summary, position_ids: [L]; text_to_aug: [n]; summary_to_aug: [J*m].
  * position_ids gives a summary token the position of its chunk's last text token (section 2.2.1).
  * Any pointer may be NULL to skip that array. */
@@ -110,7 +111,8 @@ int ksa_layout_tile_pairs(const ksa_layout *layout, int64_t *n_pairs, uint8_t *q
 
 /*
  * The prefill launch order: entry x is what workgroup x does -- the query tile (q_space[x], q_begin[x]) for
- * batch[x] and q_head[x]; q_begin[x] = -1 marks a padding workgroup that does nothing.  Consecutive workgroup
+ * batch[x] and the query heads q_head[x] .. q_head[x] + heads_per_workgroup - 1 (ksa_layout_dims);
+ * q_begin[x] = -1 marks a padding workgroup that does nothing.  Consecutive workgroup
  * ids are dealt to the 8 XCDs round-robin, so entries congruent mod 8 share an L2.  NULL arrays: count only.
  */
 int ksa_layout_launch_order(const ksa_layout *layout, int64_t *n_entries, uint8_t *q_space, int32_t *q_begin,

@@ -60,7 +60,7 @@ def lib():
         "ksa_build_layout": (C.c_int, [pp, C.POINTER(vp)]),
         "ksa_layout_destroy": (None, [vp]),
         "ksa_layout_upload": (C.c_int, [vp]),
-        "ksa_layout_dims": (C.c_int, [vp, i64p, i32p, i32p, i32p]),
+        "ksa_layout_dims": (C.c_int, [vp, i64p, i32p, i32p, i32p, i32p]),
         "ksa_layout_index_maps": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "ksa_layout_row_ranges": (C.c_int, [vp, C.c_int64, i32p]),
         "ksa_layout_mask_row": (C.c_int, [vp, C.c_int64, vp]),
@@ -126,9 +126,11 @@ class Layout:
         h = C.c_void_p()
         _check(lib().ksa_build_layout(C.byref(params), C.byref(h)), "ksa_build_layout")
         self._h = h
-        L, J, qt, kt = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32()
-        _check(lib().ksa_layout_dims(h, C.byref(L), C.byref(J), C.byref(qt), C.byref(kt)), "ksa_layout_dims")
+        L, J, qt, kt, hs = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+        _check(lib().ksa_layout_dims(h, C.byref(L), C.byref(J), C.byref(qt), C.byref(kt), C.byref(hs)),
+               "ksa_layout_dims")
         self.aug_len, self.n_chunks, self.q_tile_rows, self.k_tile_rows = L.value, J.value, qt.value, kt.value
+        self.heads_per_workgroup = hs.value
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

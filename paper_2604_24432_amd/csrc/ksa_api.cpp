@@ -92,6 +92,7 @@ int prefill_call(ksa_layout *lay, const void *q, const void *k, const void *v, v
     a.n_entries = (int32_t)lay->entries.size();
     a.n_pipelined_items = lay->n_pipelined_items;
     a.n_generic_items = (int32_t)lay->items.size() - lay->n_pipelined_items;
+    a.head_stack = lay->head_stack;
     a.p = p;
     a.aug_len = lay->aug_len;
     a.workspace = workspace;
@@ -145,6 +146,7 @@ int ksa_prefill_bwd(ksa_layout *lay, const void *q, const void *k, const void *v
     a.items = static_cast<const KsaWorkItem *>(lay->d_items);
     a.entries = static_cast<const KsaWgEntry *>(lay->d_entries);
     a.n_entries = (int32_t)lay->entries.size();
+    a.head_stack = lay->head_stack;
     a.p = p;
     a.aug_len = lay->aug_len;
     a.workspace = workspace;

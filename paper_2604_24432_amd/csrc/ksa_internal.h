@@ -14,6 +14,8 @@ struct ksa_layout {
     std::vector<KsaWorkItem> items;   // one per query tile, heaviest first
     std::vector<KsaWgEntry> entries;  // one per workgroup of the prefill launch
     int32_t n_pipelined_items = 0;    // items with KsaWorkItem::pipelined set
+    int32_t head_stack = 1;           // query heads per workgroup (1, 2 or 4)
+    int32_t q_tile_rows = KSA_Q_TILE; // rows of a query tile = KSA_Q_TILE / head_stack
     // device copies (owned), valid on `device` once uploaded
     int device = -1;
     void *d_items = nullptr;
@@ -33,6 +35,7 @@ struct KsaPrefillLaunch {
     const KsaWgEntry *entries;
     int32_t n_entries;
     int32_t n_pipelined_items, n_generic_items;   // how many work items each of the two kernels owns
+    int32_t head_stack;                           // query heads per workgroup
     ksa_params p;
     int64_t aug_len;
     void *workspace;          // key-major copy of V, written by the launch itself
@@ -50,6 +53,7 @@ struct KsaPrefillBwdLaunch {
     const KsaWorkItem *items;
     const KsaWgEntry *entries;
     int32_t n_entries;
+    int32_t head_stack;       // query heads per workgroup of the schedule
     ksa_params p;
     int64_t aug_len;
     void *workspace;          // delta_i = dO_i . O_i per (batch, query head, row), fp32

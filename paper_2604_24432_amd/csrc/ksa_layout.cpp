@@ -113,7 +113,7 @@ void build_entries(ksa_layout &lay) {
     const int32_t n_items = (int32_t)lay.items.size();
     std::vector<std::vector<KsaWgEntry>> queue(KSA_NUM_XCD);
     auto emit = [&](int q, int32_t item, int32_t grp) {
-        for (int32_t x = 0; x < gsz; ++x) {
+        for (int32_t x = 0; x < gsz; x += lay.head_stack) {
             KsaWgEntry e;
             e.item = item;
             e.batch = grp / p.n_kv_heads;
@@ -176,11 +176,17 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
     lay->n_chunks = p.n_text / p.chunk_len;
     lay->aug_len = (int64_t)lay->n_chunks * (p.chunk_len + p.n_summary) + p.n_text % p.chunk_len;
 
-    for (int64_t t0 = 0; t0 < p.n_text; t0 += KSA_Q_TILE)
-        lay->items.push_back(text_item(p, t0, (int32_t)std::min<int64_t>(KSA_Q_TILE, p.n_text - t0)));
+    // query heads per workgroup: as many heads of one KV group as divide it, up to KSA_MAX_HEAD_STACK
+    const int32_t gsz = p.n_q_heads / p.n_kv_heads;
+    lay->head_stack = gsz % 4 == 0 ? 4 : gsz % 2 == 0 ? 2 : 1;
+    static_assert(KSA_MAX_HEAD_STACK == 4, "head stacks are 1, 2 or 4");
+    lay->q_tile_rows = KSA_Q_TILE / lay->head_stack;
+    const int64_t qt = lay->q_tile_rows;
+    for (int64_t t0 = 0; t0 < p.n_text; t0 += qt)
+        lay->items.push_back(text_item(p, t0, (int32_t)std::min<int64_t>(qt, p.n_text - t0)));
     const int64_t n_sum = (int64_t)lay->n_chunks * p.n_summary;
-    for (int64_t u0 = 0; u0 < n_sum; u0 += KSA_Q_TILE)
-        lay->items.push_back(summary_item(p, u0, (int32_t)std::min<int64_t>(KSA_Q_TILE, n_sum - u0)));
+    for (int64_t u0 = 0; u0 < n_sum; u0 += qt)
+        lay->items.push_back(summary_item(p, u0, (int32_t)std::min<int64_t>(qt, n_sum - u0)));
     for (KsaWorkItem &it : lay->items) {
         it.pipelined = item_pipelined(p, it) ? 1 : 0;
         lay->n_pipelined_items += it.pipelined;
@@ -193,12 +199,13 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
 }
 
 int ksa_layout_dims(const ksa_layout *lay, int64_t *aug_len, int32_t *n_chunks, int32_t *q_tile_rows,
-                    int32_t *k_tile_rows) {
+                    int32_t *k_tile_rows, int32_t *heads_per_workgroup) {
     if (!lay) return KSA_ERR_INVALID_ARG;
     if (aug_len) *aug_len = lay->aug_len;
     if (n_chunks) *n_chunks = lay->n_chunks;
-    if (q_tile_rows) *q_tile_rows = KSA_Q_TILE;
+    if (q_tile_rows) *q_tile_rows = lay->q_tile_rows;
     if (k_tile_rows) *k_tile_rows = KSA_K_TILE;
+    if (heads_per_workgroup) *heads_per_workgroup = lay->head_stack;
     return KSA_OK;
 }
 

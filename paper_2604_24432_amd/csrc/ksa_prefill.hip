@@ -1,7 +1,8 @@
 // KSA prefill forward for gfx950: flash-style online softmax over the live key tiles of the schedule.
 //
-// One workgroup (4 wavefronts of 64 lanes, one per SIMD) owns one query tile of one (batch, query head);
-// each wave owns 32*QB query rows.  Scores are produced TRANSPOSED, S^T = K Q^T, with
+// One workgroup (4 wavefronts of 64 lanes, one per SIMD) owns one query tile of one batch entry for S query
+// heads of one KV head (S = 1, 2 or 4: the schedule's head stack); each wave owns 32*QB query rows of one head:
+// wave w takes head w % S and row block w / S of the tile, so all waves of a workgroup share their K / V tiles.  Scores are produced TRANSPOSED, S^T = K Q^T, with
 // v_mfma_f32_32x32x16_bf16: the 32x32 result block gives lane l the query column l%32 and the key rows
 // 8*(g/4) + 4*(l/32) + g%4 for its 16 registers g, so
 //   - the softmax statistics of a query row live in one lane pair (l, l^32): the row maximum is an in-lane
@@ -72,6 +73,7 @@ struct PrefillArgs {
     int32_t c, m, C, w;            // chunk_len, n_summary, window_chunks, c + m
     int32_t c_shift, m_shift;      // log2 when a power of two, else -1
     int32_t group;                 // Hq / Hkv
+    int32_t stack, stack_shift;    // query heads per workgroup (1, 2 or 4) and its log2
     int32_t n_q_heads;
     int32_t self_only;
     int64_t aug_len;
@@ -713,9 +715,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
     if ((item.pipelined != 0) != PIPELINED) return;
-    const int b = ent.batch, hq = ent.q_head, hkv = hq / a.group;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // this wave's query head and its block of 32*QB rows of the query tile
+    const int b = ent.batch, hq = ent.q_head + (wave & (a.stack - 1)), hkv = ent.q_head / a.group;
+    const int wrow = wave >> a.stack_shift;
     const int r = lane & 31, h = lane >> 5;
     const LaneLds ll = lane_lds<D>(lane);
 
@@ -729,7 +733,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     bf16x8 qreg[QB][T::KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const int idx = q_begin + (wave * QB + qb) * 32 + r;
+        const int idx = q_begin + (wrow * QB + qb) * 32 + r;
         q_valid[qb] = idx < q_end;
         const int idc = q_valid[qb] ? idx : q_end - 1;
         q_aug[qb] = aug_row(a, q_space, idc);
@@ -1135,6 +1139,9 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     a.c_shift = log2_exact(a.c);
     a.m_shift = log2_exact(a.m);
     a.group = L.p.n_q_heads / L.p.n_kv_heads;
+    a.stack = L.head_stack;
+    a.stack_shift = log2_exact(L.head_stack);
+    if (a.stack_shift < 0 || L.head_stack > KSA_MAX_HEAD_STACK || a.group % L.head_stack != 0) return KSA_ERR_INVALID_ARG;
     a.n_q_heads = L.p.n_q_heads;
     a.self_only = (L.p.flags & KSA_FLAG_SUMMARY_SELF_ONLY) ? 1 : 0;
     a.aug_len = L.aug_len;

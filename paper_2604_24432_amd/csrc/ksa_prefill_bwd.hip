@@ -49,6 +49,7 @@ struct BwdArgs {
     int32_t c, m, C, w;                       // chunk_len, n_summary, window_chunks, c + m
     int32_t c_shift, m_shift;
     int32_t group, n_q_heads, n_kv_heads, self_only, batch;
+    int32_t stack, stack_shift;    // dQ kernel: query heads per workgroup of the forward schedule (1, 2 or 4), its log2
     int32_t n_text, n_sum;                    // rows per index space
     int32_t sum_tiles;                        // dK/dV grid: summary-space key tiles come first (the long ones)
     int64_t aug_len;
@@ -226,9 +227,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
-    const int b = ent.batch, hq = ent.q_head, hkv = hq / a.group;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // as in the forward kernel: wave w takes query head w % stack and row block w / stack of the query tile
+    const int b = ent.batch, hq = ent.q_head + (wave & (a.stack - 1)), hkv = ent.q_head / a.group;
+    const int wrow = wave >> a.stack_shift;
     const int r = lane & 31, h = lane >> 5;
     const LaneLds ll = lane_lds<D>(lane);
     const int q_space = item.q_space, q_begin = item.q_begin, q_end = item.q_begin + item.q_count;
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     bf16x8 qreg[QB][KS], greg[QB][KS];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const int idx = q_begin + (wave * QB + qb) * 32 + r;
+        const int idx = q_begin + (wrow * QB + qb) * 32 + r;
         q_valid[qb] = idx < q_end;
         idc[qb] = q_valid[qb] ? idx : q_end - 1;
         q_aug[qb] = aug_row(a, q_space, idc[qb]);
@@ -769,6 +772,9 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     a.c_shift = log2_exact(a.c);
     a.m_shift = log2_exact(a.m);
     a.group = L.p.n_q_heads / L.p.n_kv_heads;
+    a.stack = L.head_stack;
+    a.stack_shift = log2_exact(L.head_stack);
+    if (a.stack_shift < 0 || L.head_stack > KSA_MAX_HEAD_STACK || a.group % L.head_stack != 0) return KSA_ERR_INVALID_ARG;
     a.n_q_heads = L.p.n_q_heads;
     a.n_kv_heads = L.p.n_kv_heads;
     a.batch = L.p.batch;

@@ -4,11 +4,14 @@
 
 #include <stdint.h>
 
-// Heights of the tiles the schedule is cut into.  A query tile is KSA_Q_TILE consecutive rows of one
-// index space (compact text indices or compact summary ordinals); a key tile is KSA_K_TILE rows.
-#ifndef KSA_Q_TILE
+// Heights of the tiles the schedule is cut into.  A workgroup of the prefill kernels owns KSA_Q_TILE (row, query
+// head) pairs: a query tile of KSA_Q_TILE / S consecutive rows of one index space (compact text indices or compact
+// summary ordinals) for S query heads that share a KV head (S = 1, 2 or 4, chosen per layout: the largest of them
+// that divides the group size).  Stacking heads rather than rows keeps every wavefront of the workgroup busy on the
+// short, chunk-aligned key runs of the mask (the sliding-chunk text, a summary row's own chunk), which a taller
+// query tile visits with most of its rows masked.  A key tile is KSA_K_TILE rows.
 #define KSA_Q_TILE 256
-#endif
+#define KSA_MAX_HEAD_STACK 4
 #define KSA_K_TILE 64
 #define KSA_MAX_SEGMENTS 2
 #define KSA_NUM_XCD 8
@@ -30,7 +33,7 @@ struct KsaSegment {
 struct KsaWorkItem {
     int32_t q_space;
     int32_t q_begin;
-    int32_t q_count;   // <= KSA_Q_TILE
+    int32_t q_count;   // <= the layout's query tile height
     int32_t n_seg;
     KsaSegment seg[KSA_MAX_SEGMENTS];
     int32_t n_tiles;   // key tiles over all segments (the item's cost)
@@ -42,7 +45,7 @@ struct KsaWorkItem {
 struct KsaWgEntry {
     int32_t item;
     int32_t batch;
-    int32_t q_head;
+    int32_t q_head;    // first of the query heads the workgroup stacks
     int32_t pad;
 };
 

@@ -214,7 +214,12 @@ def test_launch_order_lists_every_unit_once_and_groups_kv_heads_per_xcd(B, Hq, H
     units = list(zip(lo["q_space"][live].tolist(), lo["q_begin"][live].tolist(), lo["batch"][live].tolist(),
                      lo["q_head"][live].tolist()))
     n_items = n // lay.q_tile_rows + (n // c * m + lay.q_tile_rows - 1) // lay.q_tile_rows
-    assert len(units) == len(set(units)) == n_items * B * Hq
+    # a workgroup stacks as many query heads of a KV group as divide it (at most 4) on a shorter query tile
+    g = Hq // Hkv
+    assert lay.heads_per_workgroup == (4 if g % 4 == 0 else 2 if g % 2 == 0 else 1)
+    assert lay.q_tile_rows * lay.heads_per_workgroup == 256
+    assert all(h % lay.heads_per_workgroup == 0 for h in lo["q_head"][live].tolist())
+    assert len(units) == len(set(units)) == n_items * B * Hq // lay.heads_per_workgroup
     assert len(lo["q_begin"]) % 8 == 0
     # workgroups congruent mod 8 land on one XCD: with at least 8 (batch, KV head) groups an XCD never
     # shares a group with another XCD
