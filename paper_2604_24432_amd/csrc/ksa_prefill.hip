@@ -105,6 +105,7 @@ struct Tile {
     static constexpr int KS = D / 16;          // k steps of the score MFMA
     static constexpr int DB = D / 32;          // 32-column blocks of the output
     static constexpr int BYTES = BN * D * 2;
+    static constexpr int STAGE_ROW = D * 2 + 16;   // bytes per row of the epilogue's staging area (32 rows per wave)
     // pipelined loop: LDS operand reads are issued this many k steps (two MFMAs each) ahead of their use (measured:
     // four steps are 1 % faster than two; more would not fit into the 256 VGPRs next to the scores and the Q operand)
     static constexpr int RING = KS / 2 > 2 ? KS / 2 : 2;
@@ -702,7 +703,8 @@ template <int D, bool PIPELINED>
 __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs a) {
     using T = Tile<D>;
     // three K tiles, then three V tiles: the pipelined loop loads two tiles ahead with one barrier per tile
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[6 * T::BYTES];
+    // ... and the staging area of the epilogue
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[6 * T::BYTES + NW * 32 * T::STAGE_ROW];
     constexpr int K0 = 0, V0 = 3 * T::BYTES;
 
 #ifdef KSA_TRACE
@@ -1028,29 +1030,45 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     const unsigned long long TE0 = KSA_NOW();
 #endif
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
+    // The accumulators hold O transposed: a lane owns one query row and, per register group, four consecutive head-dim
+    // values, so storing them directly would scatter 8-byte pieces over 32 rows per instruction.  Each wave instead
+    // passes its 32-row blocks through a private LDS staging area (rows padded by 16 bytes against bank conflicts) and
+    // writes whole rows: one store instruction covers 1 KiB of contiguous 16-byte pieces.  Only this wave touches the
+    // area, and a wave's LDS accesses complete in order, so no barrier is needed.
+    {
+        constexpr int ROWB = T::STAGE_ROW;
+        unsigned char *stg = lds + 6 * T::BYTES + wave * (32 * ROWB);
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float l_row;
-        if (PIPELINED) {   // lane j < 16 holds the sums of queries j (register 0) and j + 16 (register 1)
-            const float s0 = __shfl(st.l_sum[qb][0], r & 15), s1 = __shfl(st.l_sum[qb][1], r & 15);
-            l_row = (r & 16) ? s1 : s0;
-        } else {
-            l_row = st.l_part[qb] + other_half(st.l_part[qb]);
-        }
-        if (!q_valid[qb]) continue;
-        const float inv = 1.0f / l_row;
-        __bf16 *op = a.o + b * a.os[0] + (int64_t)q_aug[qb] * a.os[1] + hq * a.os[2];
-#pragma unroll
-        for (int db = 0; db < T::DB; ++db)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                bf16x4 pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[qb][db][g4 * 4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + db * 32 + g4 * 8 + h * 4) = pk;
+        for (int qb = 0; qb < QB; ++qb) {
+            float l_row;
+            if (PIPELINED) {   // lane j < 16 holds the sums of queries j (register 0) and j + 16 (register 1)
+                const float s0 = __shfl(st.l_sum[qb][0], r & 15), s1 = __shfl(st.l_sum[qb][1], r & 15);
+                l_row = (r & 16) ? s1 : s0;
+            } else {
+                l_row = st.l_part[qb] + other_half(st.l_part[qb]);
             }
-        if (a.lse && h == 0)
-            a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
+            const float inv = 1.0f / l_row;   // rows past the end of the tile: never stored
+#pragma unroll
+            for (int db = 0; db < T::DB; ++db)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[qb][db][g4 * 4 + e] * inv);
+                    *reinterpret_cast<bf16x4 *>(stg + r * ROWB + (db * 32 + g4 * 8 + h * 4) * 2) = pk;
+                }
+            const int row0 = q_begin + (wrow * QB + qb) * 32;
+#pragma unroll
+            for (int i = 0; i < 32 / T::RPI; ++i) {
+                const int row = T::RPI * i + lane / T::CH, piece = lane % T::CH;
+                const u32x4 x = *reinterpret_cast<const u32x4 *>(stg + row * ROWB + piece * 16);
+                if (row0 + row < q_end)
+                    *reinterpret_cast<u32x4 *>(a.o + b * a.os[0] + (int64_t)aug_row(a, q_space, row0 + row) * a.os[1] +
+                                               hq * a.os[2] + piece * 8) = x;
+            }
+            if (a.lse && h == 0 && q_valid[qb])
+                a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
+        }
     }
 #ifdef KSA_TRACE
     tr.acc[9] = KSA_NOW() - TK0;
