@@ -46,17 +46,6 @@ static_assert(KSA_Q_TILE == NW * QB * 32, "query tile must be a whole number of 
 static_assert(BN == 64, "key tile is two 32-key MFMA blocks");
 constexpr float RESCALE_THRESHOLD_LOG2 = 8.0f;   // raise the running max only for a jump above 2^8
 
-#ifdef KSA_TRACE
-// development only: cycle counts of the pieces of the pipelined loop, summed over every wave
-__device__ unsigned long long ksa_trace_buf[16];
-struct Trace { unsigned long long acc[16]; };
-#define KSA_NOW() __builtin_readcyclecounter()
-#define KSA_TRACE_ARG , Trace &tr
-#define KSA_TRACE_PASS , tr
-#else
-#define KSA_TRACE_ARG
-#define KSA_TRACE_PASS
-#endif
 
 struct PrefillArgs {
     const __bf16 *q, *k, *v;
@@ -306,7 +295,7 @@ __device__ __forceinline__ void raise_reference_pl(RowState &st, const float (&m
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             float acc = st.l_sum[qb][i], tmp;
-            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
                          : "+a"(acc), "=&v"(tmp)
                          : "v"(i == 0 ? alpha : alpha_hi));
             st.l_sum[qb][i] = acc;
@@ -316,7 +305,7 @@ __device__ __forceinline__ void raise_reference_pl(RowState &st, const float (&m
 #pragma unroll
             for (int g = 0; g < 16; ++g) {
                 float acc = oacc[qb][db][g], tmp;
-                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1"
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
                              : "+a"(acc), "=&v"(tmp)
                              : "v"(alpha));
                 oacc[qb][db][g] = acc;
@@ -502,7 +491,7 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                                         int k_off, int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
                                         RowState &st, const u32x4 &ind, float sl, float raise_margin,
                                         float (&mx_out)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
-                                        const int (&vis_span)[QB] KSA_TRACE_ARG) {
+                                        const int (&vis_span)[QB]) {
     using T = Tile<D>;
     constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of the P V phase
     static_assert(NSTEP == T::KS, "one V operand is fetched per score step");
@@ -585,10 +574,6 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                 mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
             }
     };
-#ifdef KSA_TRACE
-    const unsigned long long T0 = KSA_NOW();
-    unsigned long long T3 = 0;
-#endif
     // ---- score slots ----
 #pragma unroll
     for (int u = 0; u < N1; ++u) {
@@ -607,11 +592,6 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         valu_slice(u);
         KSA_STEP_FENCE();
     }
-#ifdef KSA_TRACE
-    const unsigned long long T1 = KSA_NOW();
-    tr.acc[SYNC ? 0 : 4] += T1 - T0;
-    T3 = T1;
-#endif
     // ---- P V slots ----
 #pragma unroll
     for (int u = 0; u < N2; ++u) {
@@ -622,22 +602,11 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         if (qb == QB - 1 && x + RING < NSTEP) va[x % RING] = read_vt_operand(lds, lv, (x + RING) / T::DB, (x + RING) % T::DB);
         if (SYNC) {
             if (u == 0) {
-#ifdef KSA_TRACE
-                const unsigned long long T2 = KSA_NOW();
-#endif
                 __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next tile have landed
-#ifdef KSA_TRACE
-                const unsigned long long T2b = KSA_NOW();
-                tr.acc[1] += T2b - T2;
-#endif
                 // ... and everyone's; nobody still reads the buffer loaded next.  A bare s_barrier: __syncthreads() would
                 // also drain this wave's LDS operand reads in flight (lgkmcnt(0)), which belong to the current tile and
                 // may stay in flight.  The "memory" clobber keeps the reads of the published tile behind it.
                 asm volatile("s_barrier" ::: "memory");
-#ifdef KSA_TRACE
-                T3 = KSA_NOW();
-                tr.acc[2] += T3 - T2b;
-#endif
             }
             // the tile after next, one instruction per slot
             if (u >= 1 && u - 1 < T::NI) issue_tile_load_part<D>(sync.kg, sync.k_off[u - 1], sync.k_dst, u - 1);
@@ -656,9 +625,6 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
         valu_slice(N1 + u);
         KSA_STEP_FENCE();
     }
-#ifdef KSA_TRACE
-    tr.acc[SYNC ? 3 : 5] += KSA_NOW() - T3;
-#endif
     bool raise = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -707,12 +673,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[6 * T::BYTES + NW * 32 * T::STAGE_ROW];
     constexpr int K0 = 0, V0 = 3 * T::BYTES;
 
-#ifdef KSA_TRACE
-    Trace tr;
-    for (int i = 0; i < 16; ++i) tr.acc[i] = 0;
-    const unsigned long long TK0 = KSA_NOW();
-    const unsigned long long TW0 = wall_clock64();
-#endif
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
@@ -805,13 +765,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     const float sl = a.scale_log2e;
     const float raise_margin = RESCALE_THRESHOLD_LOG2 / sl;   // the rescale threshold in raw score units
 
-#ifdef KSA_TRACE
-    tr.acc[14] = KSA_NOW() - TK0;
-#endif
     for (int seg = 0; seg < n_seg; ++seg) {
-#ifdef KSA_TRACE
-        const unsigned long long TS0 = KSA_NOW();
-#endif
         const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
         // tiles inside [full_lo, full_hi) are seen whole by every row of the query tile; the others are masked
         const int full_lo = item.seg[seg].full_lo, full_hi = item.seg[seg].full_hi;
@@ -901,6 +855,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     mxl[qb] = mx;
                     raise |= mx > st.m_ref[qb] + raise_margin;
                 }
+                if (seg == 0) {
+                    // nothing has been accumulated yet, so the reference maximum simply starts at the first block's row
+                    // maximum: no rescale of the (zero) accumulators and row sums.  A row that sees none of these keys
+                    // keeps its start value and is raised by the first block it does see.
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        st.m_ref[qb] = fmaxf(st.m_ref[qb], fmaxf(mxl[qb], other_half(mxl[qb])));
+                    raise = false;
+                }
                 raise = __builtin_amdgcn_ballot_w64(raise) != 0;
                 bf16x8 ka_pre[T::RING];
 #pragma unroll
@@ -910,17 +873,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 sync.k_off = k_offb;
                 sync.v_off = v_offb;
                 sync.kg = kbase, sync.vg = vtbase, sync.k_dst = k_wave, sync.v_dst = v_wave;
-#ifdef KSA_TRACE
-                const unsigned long long TL0 = KSA_NOW();
-                tr.acc[12] += TL0 - TS0;
-#endif
                 // does some row of this wave see a key of the tile that starts at key k0?
                 auto wave_sees = [&](int k0) { return k0 < whi && k0 + BN > wlo; };
                 auto stretch = [&](auto masked_tag, int tn_begin, int tn_end) {
                     constexpr bool MASKED = decltype(masked_tag)::value;
-#ifdef KSA_TRACE
-                    const unsigned long long TT0 = KSA_NOW();
-#endif
                     for (int tn = tn_begin; tn < tn_end; ++tn) {
                         const int key0 = seg_begin + tn * BN;
                         if (tn > 0) {
@@ -933,7 +889,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                                 if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                                 raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur,
                                                                   1, K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl,
-                                                                  sync, key0, vis_lo, vis_span KSA_TRACE_PASS) &&
+                                                                  sync, key0, vis_lo, vis_span) &&
                                         (tn < n_tiles);
                             }
                             const int b_old = b_cur;
@@ -956,14 +912,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                                 if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                                 raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF,
                                                                  V0 + b_cur, 0, K0 + b_nxt, oacc, st, ind, sl, raise_margin,
-                                                                 mxl, sync, key0 + 32, vis_lo, vis_span KSA_TRACE_PASS);
+                                                                 mxl, sync, key0 + 32, vis_lo, vis_span);
                             }
                         }
                     }
-#ifdef KSA_TRACE
-                    tr.acc[MASKED ? 11 : 7] += KSA_NOW() - TT0;
-                    tr.acc[MASKED ? 15 : 6] += tn_end - tn_begin;
-#endif
                 };
                 // tiles [f_lo, f_hi) of the run are FULL
                 int f_lo = full_lo > seg_begin ? (full_lo - seg_begin + BN - 1) / BN : 0;
@@ -1018,17 +970,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             pv_mfma<D>(lds, V0, ll, pb, oacc);
         }
         }
-#ifdef KSA_TRACE
-        if (!PIPELINED) {
-            tr.acc[11] += KSA_NOW() - TS0;
-            tr.acc[15] += n_tiles;
-        }
-#endif
     }
 
-#ifdef KSA_TRACE
-    const unsigned long long TE0 = KSA_NOW();
-#endif
     // ---- epilogue: O = O^T / l, LSE ---------------------------------------------------------------
     // The accumulators hold O transposed: a lane owns one query row and, per register group, four consecutive head-dim
     // values, so storing them directly would scatter 8-byte pieces over 32 rows per instruction.  Each wave instead
@@ -1070,14 +1013,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
         }
     }
-#ifdef KSA_TRACE
-    tr.acc[9] = KSA_NOW() - TK0;
-    tr.acc[13] = KSA_NOW() - TE0;
-    tr.acc[8] = wall_clock64() - TW0;
-    tr.acc[10] = 1;
-    if (lane == 0)
-        for (int i = 0; i < 16; ++i) atomicAdd(&ksa_trace_buf[i], tr.acc[i]);
-#endif
 }
 
 // Key-major copy of V for the pipelined loop.  The P V MFMA wants, per lane, eight keys of one head-dim column; V is
@@ -1129,16 +1064,6 @@ size_t ksa_prefill_workspace_size(const ksa_params &p) {
     return (size_t)((int64_t)p.batch * p.n_kv_heads * p.head_dim * keys * 2);
 }
 
-#ifdef KSA_TRACE
-extern "C" int ksa_debug_trace(unsigned long long *out16, int reset) {
-    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(ksa_trace_buf), 16 * sizeof(unsigned long long)) != hipSuccess) return -1;
-    if (reset) {
-        unsigned long long z[16] = {0};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(ksa_trace_buf), z, sizeof(z)) != hipSuccess) return -1;
-    }
-    return 0;
-}
-#endif
 
 int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     PrefillArgs a;
