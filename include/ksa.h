@@ -39,7 +39,8 @@ typedef enum ksa_status {
     KSA_ERR_UNSUPPORTED = -2,        /* head_dim / group size the kernels were not built for        */
     KSA_ERR_WORKSPACE_TOO_SMALL = -3,
     KSA_ERR_HIP = -4,                /* a HIP runtime call failed (no device, launch error, OOM)    */
-    KSA_ERR_OUT_OF_RANGE = -5        /* an index argument lies outside the layout                   */
+    KSA_ERR_OUT_OF_RANGE = -5,       /* an index argument lies outside the layout                   */
+    KSA_ERR_SCRATCH_LIMIT = -6       /* the problem needs more than the library's static scratch buffer holds */
 } ksa_status;
 
 #define KSA_FLAG_SUMMARY_SELF_ONLY 1u /* summary rows see, among summaries, only themselves */
@@ -214,6 +215,25 @@ size_t ksa_decode_workspace_bytes(const ksa_params *params, int32_t n_splits);
 int ksa_decode_fwd(const ksa_params *params /*host*/, const void *q, const void *k_cache, const void *v_cache,
                    const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], void *workspace,
                    size_t workspace_bytes, int32_t n_splits, void *stream);
+
+/*
+ * ksa_decode_fwd_static: ksa_decode_fwd for callers that cannot allocate device memory or hand over a workspace --
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as ksa_decode_fwd (bit for bit, for the same n_splits), but the partial records of the spans live in a
+ * static device array inside the library instead of a caller workspace; the call allocates and frees nothing.
+ *   - Limit: ksa_decode_workspace_bytes(params, n_splits) must not exceed KSA_DECODE_STATIC_SCRATCH_BYTES (8 MiB;
+ *     the 128K decode workload -- batch 64, 32 query heads, 3 spans -- needs 3.2 MB); otherwise the call returns
+ *     KSA_ERR_SCRATCH_LIMIT and enqueues nothing.
+ *   - Every GPU holds its own copy of the array for the life of the process; its address is looked up on the
+ *     first call on that GPU (one hipGetSymbolAddress, no allocation).
+ *   - All calls on one GPU share the array: calls on different streams that overlap in time race on it; calls must
+ *     be stream-ordered or otherwise serialised by the caller.  The array keeps the previous call's records; every
+ *     record the merge kernel reads is rewritten by the same call's first kernel, so nothing needs clearing.
+ */
+#define KSA_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+int ksa_decode_fwd_static(const ksa_params *params /*host*/, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], int32_t n_splits,
+                          void *stream);
 
 /* ---- cache lifecycle of the decode loop (section 2.3.1, the step-by-step cache description) ----------- */
 

@@ -78,6 +78,7 @@ def lib():
         "ksa_decode_ranges": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_decode_workspace_bytes": (C.c_size_t, [pp, C.c_int32]),
         "ksa_decode_fwd": (C.c_int, [pp, vp, vp, vp, vp, vp, vp, i64p, vp, C.c_size_t, C.c_int32, vp]),
+        "ksa_decode_fwd_static": (C.c_int, [pp, vp, vp, vp, vp, vp, vp, i64p, C.c_int32, vp]),
         "ksa_decode_summary_ranges": (C.c_int, [pp, C.c_int64, i32p]),
         "ksa_decode_summary_fwd": (C.c_int, [pp, vp, vp, vp, vp, vp, vp, i64p, vp, C.c_size_t, C.c_int32, vp]),
         "ksa_cache_from_prefill": (C.c_int, [pp, C.c_int64, vp, vp, i64p, vp, vp, i64p, vp]),
@@ -97,7 +98,7 @@ EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload
                     "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v",
                     "ksa_prefill_bwd_workspace_bytes", "ksa_prefill_bwd", "ksa_cache_geometry", "ksa_cache_text_row",
                     "ksa_cache_summary_row", "ksa_decode_ranges", "ksa_decode_workspace_bytes",
-                    "ksa_decode_fwd", "ksa_decode_summary_ranges", "ksa_decode_summary_fwd", "ksa_cache_from_prefill",
+                    "ksa_decode_fwd", "ksa_decode_fwd_static", "ksa_decode_summary_ranges", "ksa_decode_summary_fwd", "ksa_cache_from_prefill",
                     "ksa_cache_append", "ksa_status_string", "ksa_build_info")
 
 
@@ -361,6 +362,34 @@ def ksa_decode_fwd(params: ksa_params, q, k_cache, v_cache, pos, o=None, lse=Non
                    workspace=None, n_splits: int = 0, stream=None):
     """q [B, Hq, d] bf16; caches [B, Hkv, cache_rows, d] bf16; pos int32 [B] on the GPU (text indices)."""
     return _decode("ksa_decode_fwd", params, q, k_cache, v_cache, pos, o, lse, return_lse, workspace, n_splits, stream)
+
+
+KSA_DECODE_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def ksa_decode_fwd_static(params: ksa_params, q, k_cache, v_cache, pos, o, lse=None, n_splits: int = 0, stream=None):
+    """ksa_decode_fwd with the spans' partial records in the library's static device array: the call allocates
+    nothing, so o (and lse, if wanted) must be passed in.  Raises KsaError (scratch limit) for problems whose
+    records exceed KSA_DECODE_STATIC_SCRATCH_BYTES."""
+    import torch
+    _require(q, "q", torch.bfloat16, 3)
+    _require(o, "o", torch.bfloat16, 3)
+    _require(pos, "pos", torch.int32, 1)
+    _check_cache(params, k_cache, v_cache)
+    if not q.is_contiguous() or not o.is_contiguous() or o.shape != q.shape:
+        raise ValueError("q and o must be contiguous and of one shape")
+    if tuple(q.shape) != (params.batch, params.n_q_heads, params.head_dim) or pos.shape[0] != params.batch:
+        raise ValueError("q / pos shape does not match params")
+    if lse is not None:
+        _require(lse, "lse", torch.float32, 2)
+        if tuple(lse.shape) != (params.batch, params.n_q_heads) or not lse.is_contiguous():
+            raise ValueError("lse must be a contiguous [B, Hq] tensor")
+    rc = lib().ksa_decode_fwd_static(C.byref(params), C.c_void_p(q.data_ptr()), C.c_void_p(k_cache.data_ptr()),
+                                     C.c_void_p(v_cache.data_ptr()), C.c_void_p(pos.data_ptr()),
+                                     C.c_void_p(o.data_ptr()), C.c_void_p(lse.data_ptr()) if lse is not None else None,
+                                     _strides3(k_cache, (0, 1, 2)), n_splits, _stream_ptr(stream))
+    _check(rc, "ksa_decode_fwd_static")
+    return o, lse
 
 
 def ksa_decode_summary_fwd(params: ksa_params, q, k_cache, v_cache, ordinal, o=None, lse=None, return_lse=True,

@@ -199,6 +199,23 @@ int ksa_decode_fwd(const ksa_params *p, const void *q, const void *k_cache, cons
                        n_splits, stream);
 }
 
+int ksa_decode_fwd_static(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *pos, void *o, float *lse, const int64_t cache_strides[3], int32_t n_splits,
+                          void *stream) {
+    // size check first (host arithmetic only), so that an oversized problem is refused even without a GPU
+    const int rc = ksa_validate_params(p);
+    if (rc != KSA_OK) return rc;
+    if (n_splits < 0 || n_splits > 1024) return KSA_ERR_INVALID_ARG;
+    const int32_t splits = n_splits == 0 ? ksa_decode_default_splits(p) : n_splits;
+    const size_t need = ksa_decode_workspace_bytes(p, splits);
+    if (need > KSA_DECODE_STATIC_SCRATCH_BYTES) return KSA_ERR_SCRATCH_LIMIT;
+    if (!q || !k_cache || !v_cache || !pos || !o) return KSA_ERR_INVALID_ARG;
+    float *buf = nullptr;
+    const int rs = ksa_decode_static_scratch(&buf);
+    if (rs != KSA_OK) return rs;
+    return decode_call(p, KSA_ROW_TEXT, q, k_cache, v_cache, pos, o, lse, cache_strides, buf, need, splits, stream);
+}
+
 int ksa_decode_summary_fwd(const ksa_params *p, const void *q, const void *k_cache, const void *v_cache,
                            const int32_t *ordinal, void *o, float *lse, const int64_t cache_strides[3],
                            void *workspace, size_t workspace_bytes, int32_t n_splits, void *stream) {

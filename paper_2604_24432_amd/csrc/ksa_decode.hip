@@ -11,7 +11,15 @@
 // a second kernel merges the spans of a sequence by log-sum-exp.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "ksa_internal.h"
+
+// Scratch memory of ksa_decode_fwd_static: the partial (o, max, sum) records of the spans, which ksa_decode_fwd
+// keeps in the caller's workspace.  Every GPU the library runs on holds its own copy of the array, at its own
+// address, until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address it returns (ksa_decode_static_scratch below) is what kernels and HIP calls are given.
+static __device__ __align__(256) unsigned char scratch[KSA_DECODE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -273,6 +281,23 @@ int ksa_decode_default_splits(const ksa_params *p) {
     if (want < 1) want = 1;
     if (want > 64) want = 64;
     return (int)want;
+}
+
+// Device address of `scratch` on the current device, resolved once per device (with that device current).
+int ksa_decode_static_scratch(float **ptr) {
+    constexpr int MAX_DEVICES = 64;
+    static void *addr[MAX_DEVICES] = {};
+    static std::mutex lock;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return KSA_ERR_HIP;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KSA_ERR_HIP;
+        addr[dev] = p;
+    }
+    *ptr = static_cast<float *>(addr[dev]);
+    return KSA_OK;
 }
 
 int ksa_launch_decode(const KsaDecodeLaunch &L, void *stream) {

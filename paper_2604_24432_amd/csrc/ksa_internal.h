@@ -75,6 +75,8 @@ struct KsaDecodeLaunch {
     ksa_params p;
 };
 int ksa_launch_decode(const KsaDecodeLaunch &a, void *stream);
+// Device address (current device) of the library's static scratch array of KSA_DECODE_STATIC_SCRATCH_BYTES bytes.
+int ksa_decode_static_scratch(float **ptr);
 
 struct KsaCacheFillLaunch {
     const void *k, *v;

@@ -366,6 +366,7 @@ const char *ksa_status_string(int status) {
         case KSA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case KSA_ERR_HIP: return "HIP runtime error";
         case KSA_ERR_OUT_OF_RANGE: return "index out of range";
+        case KSA_ERR_SCRATCH_LIMIT: return "problem exceeds the static scratch buffer";
         default: return "unknown status";
     }
 }
