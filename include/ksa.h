@@ -40,7 +40,8 @@ typedef enum ksa_status {
     KSA_ERR_WORKSPACE_TOO_SMALL = -3,
     KSA_ERR_HIP = -4,                /* a HIP runtime call failed (no device, launch error, OOM)    */
     KSA_ERR_OUT_OF_RANGE = -5,       /* an index argument lies outside the layout                   */
-    KSA_ERR_SCRATCH_LIMIT = -6       /* the problem needs more than the library's static scratch buffer holds */
+    KSA_ERR_SCRATCH_LIMIT = -6,      /* the problem needs more than the library's static scratch buffer holds */
+    KSA_ERR_OUT_OF_MEMORY = -7       /* a host allocation failed while building a layout            */
 } ksa_status;
 
 #define KSA_FLAG_SUMMARY_SELF_ONLY 1u /* summary rows see, among summaries, only themselves */
@@ -74,7 +75,8 @@ typedef struct ksa_layout ksa_layout;
  * per-row visible ranges, and the block-sparse schedule that lists, for every query tile, only the
  * key tiles that hold at least one visible pair (section 2.3: only non-zero block pairs are loaded).
  * Pure host work; touches no GPU.  *out (host) receives a new layout owned by the library.
- * Errors: INVALID_ARG for bad params (see ksa_params), UNSUPPORTED for head_dim not in {64, 128}.
+ * Errors: INVALID_ARG for bad params (see ksa_params), UNSUPPORTED for head_dim not in {64, 128},
+ * OUT_OF_MEMORY if the host cannot hold the schedule.
  */
 int ksa_build_layout(const ksa_params *params /*host*/, ksa_layout **out /*host*/);
 void ksa_layout_destroy(ksa_layout *layout);
@@ -84,6 +86,10 @@ void ksa_layout_destroy(ksa_layout *layout);
  * does this itself on first use; calling it ahead keeps the first timed call allocation-free.
  */
 int ksa_layout_upload(ksa_layout *layout);
+
+/* Rows of the augmented sequence (Eq. 1) of n_text text tokens under params' chunk_len and n_summary:
+ * (n_text / c)(c + m) + n_text mod c (params->n_text itself is not used).  For sizing the q / k / v tensors. */
+int ksa_augmented_rows(const ksa_params *params /*host*/, int64_t n_text, int64_t *rows /*host*/);
 
 /* ---- introspection (host arrays, caller-allocated) used by the bit-exact layout tests ---------- */
 
@@ -159,7 +165,7 @@ size_t ksa_prefill_bwd_workspace_bytes(const ksa_layout *layout);
 
 /*
  * ksa_prefill_bwd: gradients of ksa_prefill_fwd's output with respect to q, k and v for an upstream gradient
- * d_o = dLoss/dO (the paper's block-sparse kernel is its training kernel too, section 2.3.2; the formulas are
+ * d_o = dLoss/dO (the paper's block-sparse kernel is its training kernel too, section 2.3, Kernel Design; the formulas are
  * the derivative of the attention definition):
  *   P = exp(Q K^T * scale - lse) on visible pairs (Eq. 3), dV = P^T dO, dS = P o (dO V^T - rowsum(dO o O)),
  *   dQ = scale * dS K, dK = scale * dS^T Q; with grouped heads a KV head sums over its query heads.

@@ -252,7 +252,7 @@ int ksa_oracle_row_weights(const float *q, const float *k, int32_t B, int64_t n,
 
 /* ------------------------------------------------------------------------- */
 /* Gradients of the prefill attention (the paper's block-sparse kernel is    */
-/* its training kernel as well, section 2.3.2 and the efficiency appendix).  */
+/* its training kernel as well: section 2.3, Kernel Design; Conclusion).     */
 /* The paper prints no backward formula; this is the derivative of the       */
 /* definition above, written out.  For an upstream gradient G = dLoss/dO:    */
 /*   p_ij   = softmax weight of key j for query i (0 where masked)           */

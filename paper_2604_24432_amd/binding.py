@@ -60,6 +60,7 @@ def lib():
         "ksa_build_layout": (C.c_int, [pp, C.POINTER(vp)]),
         "ksa_layout_destroy": (None, [vp]),
         "ksa_layout_upload": (C.c_int, [vp]),
+        "ksa_augmented_rows": (C.c_int, [pp, C.c_int64, i64p]),
         "ksa_layout_dims": (C.c_int, [vp, i64p, i32p, i32p, i32p, i32p]),
         "ksa_layout_index_maps": (C.c_int, [vp, vp, vp, vp, vp, vp]),
         "ksa_layout_row_ranges": (C.c_int, [vp, C.c_int64, i32p]),
@@ -93,7 +94,7 @@ def lib():
     return L
 
 
-EXPORTED_SYMBOLS = ("ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload", "ksa_layout_dims",
+EXPORTED_SYMBOLS = ("ksa_augmented_rows", "ksa_build_layout", "ksa_layout_destroy", "ksa_layout_upload", "ksa_layout_dims",
                     "ksa_layout_index_maps", "ksa_layout_row_ranges", "ksa_layout_mask_row",
                     "ksa_layout_tile_pairs", "ksa_layout_launch_order", "ksa_prefill_workspace_bytes", "ksa_prefill_fwd", "ksa_prefill_relayout_v",
                     "ksa_prefill_bwd_workspace_bytes", "ksa_prefill_bwd", "ksa_cache_geometry", "ksa_cache_text_row",
@@ -300,6 +301,13 @@ def ksa_prefill_bwd(layout: Layout, q, k, v, o, lse, d_o, dq=None, dk=None, dv=N
     return dq, dk, dv
 
 
+def augmented_rows(params: ksa_params, n_text: int) -> int:
+    """Rows of the augmented sequence of n_text text tokens (from the library)."""
+    rows = C.c_int64()
+    _check(lib().ksa_augmented_rows(C.byref(params), n_text, C.byref(rows)), "ksa_augmented_rows")
+    return rows.value
+
+
 def cache_geometry(params: ksa_params) -> Tuple[int, int]:
     s, r = C.c_int32(), C.c_int32()
     _check(lib().ksa_cache_geometry(C.byref(params), C.byref(s), C.byref(r)), "ksa_cache_geometry")
@@ -424,7 +432,7 @@ def ksa_cache_from_prefill(params: ksa_params, n_prefill: int, k, v, k_cache, v_
     _require(k, "k", torch.bfloat16, 4)
     _require(v, "v", torch.bfloat16, 4)
     _check_cache(params, k_cache, v_cache)
-    L = n_prefill // max(params.chunk_len, 1) * (params.chunk_len + params.n_summary) + n_prefill % max(params.chunk_len, 1)
+    L = augmented_rows(params, n_prefill)
     if tuple(k.shape) != (params.batch, L, params.n_kv_heads, params.head_dim) or k.shape != v.shape or \
             k.stride() != v.stride() or k.stride(3) != 1:
         raise ValueError(f"k / v shape must be {(params.batch, L, params.n_kv_heads, params.head_dim)}")

@@ -90,6 +90,7 @@ int prefill_call(ksa_layout *lay, const void *q, const void *k, const void *v, v
     a.items = static_cast<const KsaWorkItem *>(lay->d_items);
     a.entries = static_cast<const KsaWgEntry *>(lay->d_entries);
     a.n_entries = (int32_t)lay->entries.size();
+    a.n_pipelined_entries = lay->n_pipelined_entries;
     a.n_pipelined_items = lay->n_pipelined_items;
     a.n_generic_items = (int32_t)lay->items.size() - lay->n_pipelined_items;
     a.head_stack = lay->head_stack;
@@ -272,9 +273,11 @@ int ksa_cache_append(const ksa_params *p, int32_t kind, const void *k_new, const
 }
 
 const char *ksa_build_info(void) {
-    static char info[160];
-    std::snprintf(info, sizeof(info), "libksa gfx950 q_tile=%d k_tile=%d max_segments=%d", KSA_Q_TILE, KSA_K_TILE,
-                  KSA_MAX_SEGMENTS);
+    static char info[320];
+    // the compiler is part of the description: the kernels place MFMA wait states by hand in inline assembly, and
+    // those were validated with this one
+    std::snprintf(info, sizeof(info), "libksa gfx950 q_tile=%d k_tile=%d max_segments=%d compiler=clang %s", KSA_Q_TILE,
+                  KSA_K_TILE, KSA_MAX_SEGMENTS, __clang_version__);
     return info;
 }
 

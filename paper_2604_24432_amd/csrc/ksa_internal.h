@@ -12,7 +12,8 @@ struct ksa_layout {
     int64_t aug_len;      // L
     int32_t n_chunks;     // J
     std::vector<KsaWorkItem> items;   // one per query tile, heaviest first
-    std::vector<KsaWgEntry> entries;  // one per workgroup of the prefill launch
+    std::vector<KsaWgEntry> entries;  // one per workgroup: first those of the pipelined items, then the others
+    int32_t n_pipelined_entries = 0;  // length of the first part (a multiple of 8)
     int32_t n_pipelined_items = 0;    // items with KsaWorkItem::pipelined set
     int32_t head_stack = 1;           // query heads per workgroup (1, 2 or 4)
     int32_t q_tile_rows = KSA_Q_TILE; // rows of a query tile = KSA_Q_TILE / head_stack
@@ -34,6 +35,7 @@ struct KsaPrefillLaunch {
     const KsaWorkItem *items;
     const KsaWgEntry *entries;
     int32_t n_entries;
+    int32_t n_pipelined_entries;                  // entries [0, n_pipelined_entries): the pipelined kernel's; rest: the generic one's
     int32_t n_pipelined_items, n_generic_items;   // how many work items each of the two kernels owns
     int32_t head_stack;                           // query heads per workgroup
     ksa_params p;

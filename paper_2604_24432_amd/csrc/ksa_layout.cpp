@@ -105,12 +105,13 @@ bool item_pipelined(const ksa_params &p, const KsaWorkItem &it) {
 // Launch order.  Workgroups are dealt to the 8 XCDs round-robin by workgroup id, and each XCD has its
 // own L2: queue q (workgroup ids congruent to q mod 8) is given whole (batch, KV head) groups so that the
 // workgroups running together on one XCD stream the same K/V rows, and items go heaviest first so the
-// long tiles start early (longest-processing-time order).
-void build_entries(ksa_layout &lay) {
+// long tiles start early (longest-processing-time order).  The entries of the items that the forward kernel's
+// pipelined instantiation walks come first, those of the other items after them, each part a launch of its own.
+// Appends the launch entries of items [item_lo, item_hi) to lay.entries (a whole number of rounds of 8).
+void build_entries(ksa_layout &lay, int32_t item_lo, int32_t item_hi) {
     const ksa_params &p = lay.p;
     const int32_t n_groups = p.batch * p.n_kv_heads;
     const int32_t gsz = p.n_q_heads / p.n_kv_heads;
-    const int32_t n_items = (int32_t)lay.items.size();
     std::vector<std::vector<KsaWgEntry>> queue(KSA_NUM_XCD);
     auto emit = [&](int q, int32_t item, int32_t grp) {
         for (int32_t x = 0; x < gsz; x += lay.head_stack) {
@@ -124,7 +125,7 @@ void build_entries(ksa_layout &lay) {
     };
     if (n_groups >= KSA_NUM_XCD) {
         for (int q = 0; q < KSA_NUM_XCD; ++q)
-            for (int32_t it = 0; it < n_items; ++it)
+            for (int32_t it = item_lo; it < item_hi; ++it)
                 for (int32_t grp = q; grp < n_groups; grp += KSA_NUM_XCD) emit(q, it, grp);
     } else {
         // fewer groups than XCDs: the queues congruent to grp mod n_groups share the items of group grp
@@ -132,14 +133,15 @@ void build_entries(ksa_layout &lay) {
             const int32_t grp = q % n_groups;
             const int32_t sharers = (KSA_NUM_XCD - grp + n_groups - 1) / n_groups;  // queues serving grp
             const int32_t rank = q / n_groups;
-            for (int32_t it = rank; it < n_items; it += sharers) emit(q, it, grp);
+            for (int32_t it = item_lo + rank; it < item_hi; it += sharers) emit(q, it, grp);
         }
     }
     size_t longest = 0;
     for (auto &qv : queue) longest = std::max(longest, qv.size());
-    lay.entries.assign(longest * KSA_NUM_XCD, KsaWgEntry{-1, 0, 0, 0});
+    const size_t base = lay.entries.size();
+    lay.entries.resize(base + longest * KSA_NUM_XCD, KsaWgEntry{-1, 0, 0, 0});
     for (int q = 0; q < KSA_NUM_XCD; ++q)
-        for (size_t x = 0; x < queue[q].size(); ++x) lay.entries[x * KSA_NUM_XCD + q] = queue[q][x];
+        for (size_t x = 0; x < queue[q].size(); ++x) lay.entries[base + x * KSA_NUM_XCD + q] = queue[q][x];
 }
 
 }  // namespace
@@ -168,7 +170,9 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
     const int rc = ksa_validate_params(params);
     if (rc != KSA_OK) return rc;
     ksa_layout *lay = new (std::nothrow) ksa_layout();
-    if (!lay) return KSA_ERR_INVALID_ARG;
+    if (!lay) return KSA_ERR_OUT_OF_MEMORY;
+    // the schedule grows std::vectors: no exception may leave through the C boundary
+    try {
     lay->p = *params;
     if (lay->p.softmax_scale <= 0.f) lay->p.softmax_scale = 1.0f / std::sqrt((float)params->head_dim);
     if (lay->p.n_summary == 0) lay->p.compress_ratio = 0;
@@ -191,10 +195,23 @@ int ksa_build_layout(const ksa_params *params, ksa_layout **out) {
         it.pipelined = item_pipelined(p, it) ? 1 : 0;
         lay->n_pipelined_items += it.pipelined;
     }
-    std::stable_sort(lay->items.begin(), lay->items.end(),
-                     [](const KsaWorkItem &a, const KsaWorkItem &b) { return a.n_tiles > b.n_tiles; });
-    build_entries(*lay);
+    std::stable_sort(lay->items.begin(), lay->items.end(), [](const KsaWorkItem &a, const KsaWorkItem &b) {
+        return a.pipelined != b.pipelined ? a.pipelined > b.pipelined : a.n_tiles > b.n_tiles;
+    });
+    build_entries(*lay, 0, lay->n_pipelined_items);
+    lay->n_pipelined_entries = (int32_t)lay->entries.size();
+    build_entries(*lay, lay->n_pipelined_items, (int32_t)lay->items.size());
+    } catch (...) {
+        delete lay;
+        return KSA_ERR_OUT_OF_MEMORY;
+    }
     *out = lay;
+    return KSA_OK;
+}
+
+int ksa_augmented_rows(const ksa_params *p, int64_t n_text, int64_t *rows) {
+    if (!p || !rows || n_text < 0 || p->chunk_len <= 0 || p->n_summary < 0) return KSA_ERR_INVALID_ARG;
+    *rows = n_text / p->chunk_len * (int64_t)(p->chunk_len + p->n_summary) + n_text % p->chunk_len;
     return KSA_OK;
 }
 
@@ -367,6 +384,7 @@ const char *ksa_status_string(int status) {
         case KSA_ERR_HIP: return "HIP runtime error";
         case KSA_ERR_OUT_OF_RANGE: return "index out of range";
         case KSA_ERR_SCRATCH_LIMIT: return "problem exceeds the static scratch buffer";
+        case KSA_ERR_OUT_OF_MEMORY: return "out of host memory";
         default: return "unknown status";
     }
 }

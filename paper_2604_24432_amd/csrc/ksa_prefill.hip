@@ -1120,13 +1120,16 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
         if (hipGetLastError() != hipSuccess) return KSA_ERR_HIP;
     }
     if (!(L.phases & 2)) return KSA_OK;
-    const dim3 grid(L.n_entries), block(NW * 64);
+    // the pipelined items' workgroups first, then those of the remaining items: one launch each
+    const dim3 block(NW * 64), grid_p(L.n_pipelined_entries), grid_g(L.n_entries - L.n_pipelined_entries);
+    PrefillArgs g = a;
+    g.entries = a.entries + L.n_pipelined_entries;
     if (L.p.head_dim == 128) {
-        if (L.n_pipelined_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, true>), grid, block, 0, st, a);
-        if (L.n_generic_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, false>), grid, block, 0, st, a);
+        if (grid_p.x > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, true>), grid_p, block, 0, st, a);
+        if (grid_g.x > 0) hipLaunchKernelGGL((ksa_prefill_kernel<128, false>), grid_g, block, 0, st, g);
     } else if (L.p.head_dim == 64) {
-        if (L.n_pipelined_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, true>), grid, block, 0, st, a);
-        if (L.n_generic_items > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, false>), grid, block, 0, st, a);
+        if (grid_p.x > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, true>), grid_p, block, 0, st, a);
+        if (grid_g.x > 0) hipLaunchKernelGGL((ksa_prefill_kernel<64, false>), grid_g, block, 0, st, g);
     } else {
         return KSA_ERR_UNSUPPORTED;
     }

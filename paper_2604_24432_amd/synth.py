@@ -42,8 +42,8 @@ class KsaConfig:
 
     @property
     def aug_len(self) -> int:
-        # an incomplete last chunk has text rows only
-        return self.n_chunks * (self.chunk_len + self.n_summary) + self.n_text % self.chunk_len
+        # rows of the generated tensors: every text token plus the summary tokens of the whole chunks
+        return self.n_text + self.n_chunks * self.n_summary
 
     @property
     def compress_ratio(self) -> int:
