@@ -35,8 +35,12 @@ inline void summary_row_ranges(const ksa_params &p, int64_t u, int32_t out[4]) {
 
 inline int32_t tiles_in(const KsaSegment &s) { return (s.end - s.begin + KSA_K_TILE - 1) / KSA_K_TILE; }
 
+// The run starts at the multiple of 16 at or below its first visible key: the kernel's pipelined loop wants that
+// alignment (see item_pipelined), and the up to 15 extra keys in front lie outside every row's visible range, so
+// the first tile stays live and its mask clips them.
 void push_segment(KsaWorkItem &it, int32_t space, int64_t begin, int64_t end, int64_t full_lo, int64_t full_hi) {
     if (end <= begin) return;
+    begin -= begin % 16;
     KsaSegment &s = it.seg[it.n_seg++];
     s.space = space;
     s.begin = (int32_t)begin;

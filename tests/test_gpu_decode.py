@@ -88,6 +88,8 @@ def test_decode_split_counts(n_splits):
     ("d64_gqa8", 2, 8, 1, 64, 128 * 12, 128, 16, 1, [128 * 11 + 100, 5]),
     ("gqa1_odd_chunk", 2, 2, 2, 128, 20 * 30, 20, 5, 2, [20 * 29 + 19, 20 * 3 + 7]),
     ("no_summaries", 2, 2, 1, 128, 32 * 10, 32, 0, 2, [32 * 9 + 4, 32 * 1 + 9]),
+    # token-level sliding window of 256 tokens: chunks of one token, a ring of 256 rows
+    ("token_window_w256", 3, 4, 2, 128, 2000, 1, 0, 255, [1999, 100, 255]),
 ], ids=lambda c: c[0])
 def test_decode_shapes(case):
     name, B, Hq, Hkv, d, n_cap, c, m, C, positions = case

@@ -125,6 +125,11 @@ SMALL = [
     ("ragged_tail_short", 2, 2, 2, 64, 100, 64, 8, 1),
     ("ragged_tail_m1", 1, 2, 1, 128, 1003, 8, 1, 16),
     ("less_than_a_chunk", 1, 2, 2, 128, 37, 64, 8, 1),
+    # token-level sliding window attention of width w (the paper's SWA baseline): chunks of one token, C = w - 1
+    ("token_window_w100", 1, 4, 2, 128, 700, 1, 0, 99),
+    ("token_window_w64_d64", 2, 2, 2, 64, 333, 1, 0, 63),
+    # the paper's model shapes with 16 query and 16 KV heads (no grouping: one head per workgroup)
+    ("heads16_16", 1, 16, 16, 128, 768, 8, 1, 16),
 ]
 
 
@@ -239,6 +244,8 @@ MEDIUM = [
     ("sliding_8k", 1, 2, 1, 128, 8192, 64, 0, 7, 0.0),
     ("dense_4k", 1, 2, 2, 128, 4096, 4096, 0, 0, 0.01),
     ("ragged_8k", 1, 4, 2, 128, 8192 + 37, 64, 8, 1, 0.0),
+    ("token_window_8k_w1024", 1, 4, 1, 128, 8192, 1, 0, 1023, 0.01),
+    ("heads16_16_paper_form_4k", 1, 16, 16, 128, 4096, 8, 1, 128, 0.0),
 ]
 
 
@@ -251,6 +258,24 @@ def test_medium_shapes_sampled_rows(case):
 
 def test_prefill_128k_sampled_rows():
     sampled_compare(synth.CONFIGS["prefill_128k"], n_random=160)
+
+
+def test_prefill_128k_paper_shape_sampled_rows():
+    """The shape bench.py times as paper_shape_reference: the paper's own form, one summary per chunk of 8 tokens and a
+    window of 128 chunks, at 128K."""
+    cfg = synth.CONFIGS["prefill_128k"].scaled(name="paper_shape_128k", chunk_len=8, n_summary=1, window_chunks=128,
+                                               seed=4100)
+    sampled_compare(cfg, n_random=96)
+
+
+@pytest.mark.parametrize("C", [32, 64, 128, 256])
+@pytest.mark.parametrize("c", [8, 16, 32, 64])
+def test_ablation_grid_sampled_rows(c, C):
+    """The paper's design ablations: sliding chunk number in {32, 64, 128, 256} x chunk size in {8, 16, 32, 64}, one
+    summary token per chunk, at about 6K text tokens (longer than the largest window only for the smaller settings:
+    the others exercise the window-covers-everything end)."""
+    cfg = synth.KsaConfig(f"ablation_c{c}_C{C}", 1, 4, 2, 128, 6144, c, 1, C, seed=7000 + c + C)
+    sampled_compare(cfg, n_random=96)
 
 
 def closed_form_row_counts(cfg):

@@ -81,6 +81,8 @@ SMALL = [
     ("ragged_tail", 1, 4, 2, 128, 600, 64, 8, 1),
     ("ragged_tail_m1", 1, 2, 1, 128, 1003, 8, 1, 16),
     ("less_than_a_chunk", 1, 2, 2, 128, 37, 64, 8, 1),
+    ("token_window_w100", 1, 4, 2, 128, 700, 1, 0, 99),   # token-level sliding window: chunks of one token
+    ("heads16_16", 1, 16, 16, 128, 768, 8, 1, 16),
 ]
 
 

@@ -100,7 +100,8 @@ def tile_cover(lay, n, c, m):
 
 @pytest.mark.parametrize("shape", [(512, 64, 8, 1), (384, 64, 8, 0), (384, 64, 8, 2), (640, 128, 16, 1),
                                    (320, 64, 8, 9), (200, 8, 1, 3), (300, 20, 5, 1), (252, 12, 3, 2),
-                                   (96, 96, 0, 0), (256, 16, 0, 2), (1024, 8, 1, 16), (1024, 8, 1, 128)])
+                                   (96, 96, 0, 0), (256, 16, 0, 2), (1024, 8, 1, 16), (1024, 8, 1, 128),
+                                   (300, 1, 0, 40), (200, 1, 0, 130)])
 def test_tile_schedule_covers_every_visible_pair_exactly_once(shape):
     n, c, m, C = shape
     lay = K.ksa_build_layout(params_for(n, c, m, C))

@@ -73,6 +73,20 @@ def test_no_summaries_is_chunk_aligned_sliding_window(c, Cw):
     assert np.abs(lse - ref_lse).max() < 1e-12
 
 
+@pytest.mark.parametrize("w", [1, 5, 16, 100])
+def test_token_window_attention_is_band_masked_softmax(w):
+    """Token-level sliding window attention of width w (chunk size 1, no summaries, C = w - 1) against numpy's
+    softmax under the band mask i - w < k <= i."""
+    n = 48
+    q, k, v = rand_qkv(2, n, 4, 2, 16, seed=30 + w)
+    o, lse = O.prefill(q, k, v, n=n, c=1, m=0, Cw=w - 1)
+    i = np.arange(n)
+    band = (i[None, :] <= i[:, None]) & (i[:, None] - i[None, :] < w)
+    ref_o, ref_lse = masked_attention_numpy(q, k, v, band, 1 / math.sqrt(16))
+    assert np.abs(o - ref_o).max() < 1e-12
+    assert np.abs(lse - ref_lse).max() < 1e-12
+
+
 def test_window_covering_everything_with_summaries():
     """With C >= J-1 Eq. 3's summary range is empty: text rows are dense causal attention over the
     text-only subsequence; summary rows are a softmax over their own chunk."""
