@@ -44,6 +44,65 @@ def measured_traffic(which):
     return None
 
 
+def kernel_source_digest():
+    """sha256 over the sources of the prefill and decode kernels and of the schedule they walk: profiles/hbm_traffic.txt
+    records the digest it was measured with, and a measurement taken with other sources is not reported."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    h = hashlib.sha256()
+    for name in ("ksa_prefill.hip", "ksa_decode.hip", "ksa_layout.cpp", "ksa_schedule.h", "ksa_device.h"):
+        h.update(open(os.path.join(here, "paper_2604_24432_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic_checked(which):
+    """(bytes or None, note): the measured HBM traffic if profiles/hbm_traffic.txt was taken with the present sources."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    digest, commit = None, None
+    try:
+        for line in open(path):
+            if line.startswith("kernel_source_digest:"):
+                digest = line.split(":")[1].strip()
+            if line.startswith("measured_at_commit:"):
+                commit = line.split(":")[1].strip()
+    except OSError:
+        return None, "profiles/hbm_traffic.txt missing"
+    if digest != kernel_source_digest():
+        return None, f"profiles/hbm_traffic.txt was measured with other kernel sources (commit {commit}): not reported"
+    return measured_traffic(which), f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at commit {commit} (profiles/hbm_traffic.txt)"
+
+
+def achievable_rates(read_buffer):
+    """The two 'achievable' figures beside the nominal peaks, measured now on this machine by libksa_probe.so: a loop of
+    nothing but the prefill kernel's MFMA instruction on every SIMD (one wave per SIMD, as the prefill kernel runs), and
+    a streaming read of the decode cache with the decode kernel's access pattern."""
+    import ctypes as C
+    here = os.path.dirname(os.path.abspath(__file__))
+    lib = C.CDLL(os.path.join(here, "paper_2604_24432_amd", "libksa_probe.so"))
+    lib.ksa_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.ksa_probe_read.argtypes = [C.c_void_p, C.c_longlong, C.c_int, C.POINTER(C.c_float)]
+    out = {}
+    for waves in (1, 2):
+        tf, mhz = C.c_float(), C.c_float()
+        # 20000 rounds x 8 MFMAs x 32 clocks = 5.1 M clocks per launch, 100 launches: about a quarter of a second
+        rc = lib.ksa_probe_mfma(0, waves, 20000, 100, C.byref(tf), C.byref(mhz))
+        if rc != 0:
+            raise RuntimeError(f"ksa_probe_mfma failed ({rc})")
+        out[f"mfma_only_tflops_{waves}_wave_per_simd"] = round(tf.value, 1)
+        out[f"mfma_only_core_mhz_{waves}_wave_per_simd"] = round(mhz.value, 0)
+    gbs = C.c_float()
+    nbytes = read_buffer.numel() * read_buffer.element_size() // 16 * 16
+    rc = lib.ksa_probe_read(C.c_void_p(read_buffer.data_ptr()), nbytes, 5, C.byref(gbs))
+    if rc != 0:
+        raise RuntimeError(f"ksa_probe_read failed ({rc})")
+    out["stream_read_gbs"] = round(gbs.value, 1)
+    out["stream_read_bytes"] = nbytes
+    out["note"] = ("mfma_only: v_mfma_f32_32x32x16_bf16 back to back on all SIMDs, bf16 operands of magnitude 0.25 - 4 that "
+                   "differ per lane, no memory traffic; the core clock is the kernel's own cycle counter against the "
+                   "100 MHz wall counter.  stream_read: 16-byte non-temporal loads over the decode K cache")
+    return out
+
+
 def time_events(fn, steps):
     import torch
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
@@ -72,6 +131,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--power-probe", type=float, default=0.0, metavar="SECONDS",
+                    help="loop the 128K prefill for this long while sampling the board's power and clocks with rocm-smi, "
+                         "print the samples as one JSON line and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -132,6 +194,20 @@ def main():
         prefill()
         decode()
 
+    if args.power_probe > 0:
+        res = {"prefill_128k": power_probe(prefill, args.power_probe)}
+        import ctypes as C
+        plib = C.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_24432_amd", "libksa_probe.so"))
+        plib.ksa_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        tf, mhz = C.c_float(), C.c_float()
+        # one call = 41 launches of about 2.8 ms: the same board state as the prefill loop, but nothing except MFMAs
+        res["mfma_only_loop"] = power_probe(lambda: plib.ksa_probe_mfma(0, 1, 20000, 4, C.byref(tf), C.byref(mhz)),
+                                            args.power_probe)
+        res["mfma_only_loop"]["tflops_last_call"] = round(tf.value, 1)
+        res["mfma_only_loop"]["core_mhz_last_call"] = round(mhz.value, 0)
+        print(json.dumps(res), flush=True)
+        return
+
     if args.backward_only:
         prefill()
         print(json.dumps({"prefill_backward": prefill_backward(cfg, lay, q, k, v, o, lse, max(args.steps, 1))}), flush=True)
@@ -169,6 +245,13 @@ def main():
         + 2.0 * dcfg.batch * dcfg.n_q_heads * dcfg.head_dim * 2
     dec_gbs = dec_bytes / (dec_avg * 1e-3) / 1e9
 
+    tp = lay.tile_pairs()
+    issued_pairs = int((tp["q_count"].astype(np.int64) * tp["k_count"]).sum())   # per (batch, head): padded tile area
+    issued_flops = 4.0 * cfg.head_dim * cfg.batch * cfg.n_q_heads * issued_pairs
+    pre_traffic, pre_traffic_note = measured_traffic_checked("prefill")
+    dec_traffic, _ = measured_traffic_checked("decode")
+    ach = achievable_rates(k_cache)
+
     out = {
         "metric": "KSA prefill live-TFLOP/s + %MFMA peak @128K; decode HBM GB/s + %peak",
         "value": round(pre_tflops, 2),
@@ -182,16 +265,22 @@ def main():
                    "layout_build_ms": round(layout_ms, 2), "build": K.build_info()},
         "prefill": {"ms": round(pre_avg, 4), "ms_min": round(float(np.min(pre_ms)), 4), "live_flops": live_flops,
                     "live_tflops": round(pre_tflops, 2), "frac_mfma_peak": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "relayout_v_kernel_ms": round(vt_avg, 4), "attention_kernel_ms": round(attn_avg, 4)},
+                    "relayout_v_kernel_ms": round(vt_avg, 4), "attention_kernel_ms": round(attn_avg, 4),
+                    "tile_issued_flops": issued_flops, "issued_over_live": round(issued_flops / live_flops, 4),
+                    "heads_per_workgroup": lay.heads_per_workgroup, "q_tile_rows": lay.q_tile_rows},
         "decode": {"ms": round(dec_avg, 5), "ms_min": round(float(np.min(dec_ms)), 5), "bytes": dec_bytes,
                    "gbs": round(dec_gbs, 1), "frac_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4),
                    "visible_rows_per_kv_head": vis_rows},
         "roofline": {"bound": "mfma", "kernel": "ksa_prefill_kernel<128, true>", "achieved": round(attn_tflops, 2),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": measured_traffic("prefill")},
+                     "frac": round(attn_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": pre_traffic,
+                     "traffic_source": pre_traffic_note,
+                     "frac_of_mfma_only_loop": round(attn_tflops / ach["mfma_only_tflops_1_wave_per_simd"], 4)},
         "roofline_decode": {"bound": "hbm", "kernel": "ksa_decode_split_kernel<128,4>", "achieved": round(dec_gbs, 1),
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
-                            "traffic": measured_traffic("decode")},
+                            "traffic": dec_traffic,
+                            "frac_of_stream_read": round(dec_gbs / ach["stream_read_gbs"], 4)},
+        "achievable": ach,
     }
 
     if args.hot_path_only:
@@ -203,9 +292,58 @@ def main():
         del k_cache, v_cache
         out["full_attention_reference"] = full_attention_reference(cfg, q, k, v, pre_avg)
         out["paper_shape_reference"] = paper_shape_reference(cfg)
+        out["sca_reference"] = sca_reference(cfg)
+        out["swa_reference"] = swa_reference(cfg)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, o, live_flops / live)
     print(json.dumps(out), flush=True)
+
+
+def power_probe(launch, seconds):
+    """Keeps the GPU busy with `launch` for `seconds` while a thread samples `amd-smi metric -p -c` (a read-only
+    query: socket power and the core clock of every XCD); returns the samples taken after the first second (the
+    clocks need a moment to settle)."""
+    import subprocess
+    import threading
+    import torch
+    samples, stop = [], threading.Event()
+
+    def sampler():
+        t0 = time.perf_counter()
+        while not stop.is_set():
+            rec = {"t": round(time.perf_counter() - t0, 2)}
+            try:
+                txt = subprocess.run(["amd-smi", "metric", "-g", "0", "-p", "-c", "--json"], capture_output=True, text=True,
+                                     timeout=20).stdout
+                data = json.loads(txt)
+                gpu = (data["gpu_data"] if isinstance(data, dict) else data)[0]
+                rec["socket_power_w"] = gpu["power"]["socket_power"]["value"]
+                clks = [v["clk"]["value"] for k, v in gpu["clock"].items() if k.startswith("gfx_") and isinstance(v, dict)
+                        and isinstance(v.get("clk"), dict) and isinstance(v["clk"].get("value"), (int, float))]
+                if clks:
+                    rec["gfx_clk_mhz_mean"] = round(sum(clks) / len(clks), 1)
+                    rec["gfx_clk_mhz_min"], rec["gfx_clk_mhz_max"] = min(clks), max(clks)
+                    rec["gfx_max_clk_mhz"] = gpu["clock"]["gfx_0"]["max_clk"]["value"]
+            except Exception as e:       # the probe must not take the benchmark down
+                rec["error"] = f"{type(e).__name__}: {e}"
+                samples.append(rec)
+                break
+            samples.append(rec)
+            time.sleep(0.2)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0, n = time.perf_counter(), 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            launch()
+        torch.cuda.synchronize()
+        n += 10
+    busy = time.perf_counter() - t0
+    stop.set()
+    th.join()
+    kept = [s for s in samples if s.get("t", 0) >= 1.0 and s.get("t", 0) <= busy]
+    return {"launches": n, "busy_seconds": round(busy, 2), "ms_per_launch": round(busy * 1e3 / n, 3), "samples": kept}
 
 
 def prefill_backward(cfg, lay, q, k, v, o, lse, steps):
@@ -275,14 +413,14 @@ def full_attention_reference(cfg, q, k, v, ksa_ms):
             "backward_frac_mfma_peak": round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
-def paper_shape_reference(cfg):
-    """Not part of the timed step: the paper's own chunk form at the same length and heads (one summary per chunk of 8
-    text tokens, 128 chunks of sliding window: Table of model hyper-parameters), through the same library."""
+def mask_reference(cfg, label, c, m, C, note, with_backward=True):
+    """Not part of the timed step: another mask of the paper at the benchmark's length and heads through the same
+    library (seeded N(0,1) inputs of that shape)."""
     import torch
     import paper_2604_24432_amd as K
     from paper_2604_24432_amd import synth
-    pc = synth.KsaConfig("paper_shape_128k", cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_text, 8, 1, 128,
-                         seed=cfg.seed + 50)
+    pc = synth.KsaConfig(label, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_text, c, m, C,
+                         seed=cfg.seed + 50 + c + C)
     p = K.make_params(pc.batch, pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks, pc.n_q_heads, pc.n_kv_heads,
                       pc.head_dim)
     lay = K.ksa_build_layout(p)
@@ -294,12 +432,32 @@ def paper_shape_reference(cfg):
     K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws)
     ms = float(np.mean(time_events(lambda: K.ksa_prefill_fwd(lay, q, k, v, o=o, lse=lse, workspace=ws), 5)))
     flops = 4.0 * pc.head_dim * pc.batch * pc.n_q_heads * live_pairs(pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks)
-    bwd_ms = backward_of(lay, q, k, v, o, lse, pc.seed + 7)
-    return {"workload": f"B{pc.batch} Hq{pc.n_q_heads} Hkv{pc.n_kv_heads} d{pc.head_dim} n{pc.n_text} c8 m1 C128, L={pc.aug_len}",
-            "ms": round(ms, 3), "live_flops": flops, "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
-            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "backward_ms": round(bwd_ms, 2),
-            "backward_frac_mfma_peak": round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    out = {"workload": f"{note}: B{pc.batch} Hq{pc.n_q_heads} Hkv{pc.n_kv_heads} d{pc.head_dim} n{pc.n_text} c{c} m{m} C{C}, "
+                       f"L={pc.aug_len}",
+           "ms": round(ms, 3), "live_flops": flops, "live_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+           "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    if with_backward:
+        bwd_ms = backward_of(lay, q, k, v, o, lse, pc.seed + 7)
+        out["backward_ms"] = round(bwd_ms, 2)
+        out["backward_frac_mfma_peak"] = round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+    return out
+
+
+def paper_shape_reference(cfg):
+    """The paper's own chunk form (one summary per chunk of 8 text tokens, 128 chunks of sliding window: table of model
+    hyper-parameters)."""
+    return mask_reference(cfg, "paper_shape_128k", 8, 1, 128, "KSA in the paper's own form")
+
+
+def sca_reference(cfg):
+    """Sliding Chunk Attention alone (Eq. 2: the paper's Hybrid-SCA baseline layers), chunks of 8, 128 sliding chunks."""
+    return mask_reference(cfg, "sca_128k", 8, 0, 128, "sliding chunk attention, no summaries (Eq. 2)", with_backward=False)
+
+
+def swa_reference(cfg):
+    """Token-level sliding window attention (the paper's Hybrid-SWA baseline layers) of the same span, 1024 tokens:
+    chunks of one token, 1023 previous ones visible."""
+    return mask_reference(cfg, "swa_128k", 1, 0, 1023, "token-level sliding window of 1024 tokens", with_backward=False)
 
 
 def cache_lifecycle(cfg, p, k, v, dcfg, dp, dq, k_cache, v_cache, ws, args):

@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libksa.so")
+PROBE_LIB = os.path.join(HERE, "libksa_probe.so")   # bench.py's measurement probes (csrc/ksa_probe.hip), not the product
 SOURCES = ["ksa_layout.cpp", "ksa_api.cpp", "ksa_prefill.hip", "ksa_prefill_bwd.hip", "ksa_decode.hip", "ksa_cache.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -49,6 +50,7 @@ def build(verbose: bool = False, extra=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed:\n" + out)
     out += _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    out += _run([HIPCC, *FLAGS, *extra, "-shared", "-x", "hip", os.path.join(CSRC, "ksa_probe.hip"), "-o", PROBE_LIB])
     if verbose and out.strip():
         print(out)
     return LIB
