@@ -276,8 +276,13 @@ const char *ksa_build_info(void) {
     static char info[320];
     // the compiler is part of the description: the kernels place MFMA wait states by hand in inline assembly, and
     // those were validated with this one
-    std::snprintf(info, sizeof(info), "libksa gfx950 q_tile=%d k_tile=%d max_segments=%d compiler=clang %s", KSA_Q_TILE,
-                  KSA_K_TILE, KSA_MAX_SEGMENTS, __clang_version__);
+#ifdef __clang_version__
+    const char *compiler = "clang " __clang_version__;
+#else
+    const char *compiler = "not hipcc (host-only test build)";
+#endif
+    std::snprintf(info, sizeof(info), "libksa gfx950 q_tile=%d k_tile=%d max_segments=%d compiler=%s", KSA_Q_TILE,
+                  KSA_K_TILE, KSA_MAX_SEGMENTS, compiler);
     return info;
 }
 
