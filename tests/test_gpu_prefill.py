@@ -354,6 +354,18 @@ def test_relayout_v_is_the_documented_permutation(name):
     assert np.array_equal(got, want)
 
 
+def test_repeatable_32k_outlier_keys():
+    """The pipelined loop with its hand-placed MFMA wait states on the 32K workload (outlier keys: the rescale path
+    runs): two calls give identical bits."""
+    cfg = synth.CONFIGS["prefill_32k"]
+    q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
+    lay = K.ksa_build_layout(params_of(cfg))
+    o1, l1 = K.ksa_prefill_fwd(lay, q, k, v)
+    o2, l2 = K.ksa_prefill_fwd(lay, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
 def test_repeatable():
     cfg = synth.CONFIGS["prefill_4k"]
     q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
