@@ -92,10 +92,15 @@ KsaWorkItem summary_item(const ksa_params &p, int64_t u0, int32_t cnt) {
 // offsets once per run and reads V from a key-major copy whose keys are permuted in groups of 16, so it needs
 //   - tiles that all start at the same phase of the chunk pattern (64 % period == 0) or never cross a chunk
 //     (period % 64 == 0 and an aligned start), period = c for text keys and m for summary keys,
-//   - a run that starts at a multiple of 16, and
-//   - a last tile that ends inside the index space (all 64 rows of every tile exist).
+//   - a run that starts at a multiple of 16,
+//   - a last tile that ends inside the index space (all 64 rows of every tile exist), and
+//   - a chunk length and a summary count that are powers of two.
 bool item_pipelined(const ksa_params &p, const KsaWorkItem &it) {
     const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
+    // ... and chunk shapes that are powers of two: that loop maps compact indices to rows with shifts, in scalar code
+    // it can afford inside an MFMA slot
+    auto pow2 = [](int64_t x) { return x > 0 && (x & (x - 1)) == 0; };
+    if (!pow2(p.chunk_len) || (p.n_summary > 0 && !pow2(p.n_summary))) return false;
     for (int s = 0; s < it.n_seg; ++s) {
         const KsaSegment &g = it.seg[s];
         const int64_t period = g.space == KSA_SPACE_TEXT ? p.chunk_len : p.n_summary;

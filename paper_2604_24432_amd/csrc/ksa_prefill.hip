@@ -485,13 +485,13 @@ __device__ __forceinline__ unsigned pack_pair(float w0, float w1) {
 // SYNC the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true
 // if some lane's next scores exceed its reference maximum by more than the threshold; mx_out holds the lane's maxima
 // (the lane pair of a row is only combined when a raise happens).
-template <int D, bool SYNC, bool MASKED>
+template <int D, bool SYNC, bool MASKED, class Hook>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
                                         f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::RING],
                                         int k_off, int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
                                         RowState &st, const u32x4 &ind, float sl, float raise_margin,
                                         float (&mx_out)[QB], const TileSync<D> &sync, int next_key0, const int (&vis_lo)[QB],
-                                        const int (&vis_span)[QB]) {
+                                        const int (&vis_span)[QB], Hook hook) {
     using T = Tile<D>;
     constexpr int NSTEP = 2 * T::DB;              // (hf, db) pairs of the P V phase
     static_assert(NSTEP == T::KS, "one V operand is fetched per score step");
@@ -503,7 +503,9 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                                                   // N1 + NH (a raw MFMA must not read a register a VALU instruction has
                                                   // only just written)
     constexpr int R_FIRST = N1 + 4;               // first slot that may read sv_next (four MFMAs behind its last MFMA)
-    constexpr int R_SLOTS = N1 + N2 - 1 - R_FIRST;
+    constexpr int R_SLOTS = N1 + N2 - 3 - R_FIRST;   // the row maxima are complete two slots before the end, where the
+                                                      // "raise the reference?" decision is taken: in the shadow of the
+                                                      // last MFMAs rather than behind them, with the matrix pipe idle
     constexpr int NR = QB * 8;                    // row-maximum units (two scores each)
     static_assert(E_SLOTS >= 1 && R_SLOTS >= 1, "the phases are too short for the pipelined VALU stream");
     static_assert((NE / 2 - 1) * E_SLOTS / NE + 2 <= N1 - 2, "the first half's weights are not packed in time");
@@ -590,9 +592,13 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
             }
         }
         valu_slice(u);
+        // the caller's scalar bookkeeping for the NEXT sub-tile (tile addresses, loop state) rides in the shadow of
+        // this sub-tile's second MFMA instead of sitting between two sub-tiles with the matrix pipe idle
+        if (u == 1) hook();
         KSA_STEP_FENCE();
     }
     // ---- P V slots ----
+    bool raise_any = false;
 #pragma unroll
     for (int u = 0; u < N2; ++u) {
         const int x = u / QB, qb = u % QB;
@@ -623,15 +629,18 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
             for (int q2 = 0; q2 < QB; ++q2) scores_ready(sv_next[q2]);
         }
         valu_slice(N1 + u);
+        if (u == N2 - 2) {
+            bool raise = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                mx_out[qb] = mx[qb];
+                raise |= mx[qb] > st.m_ref[qb] + raise_margin;   // (mx - m_ref) * sl > threshold
+            }
+            raise_any = __builtin_amdgcn_ballot_w64(raise) != 0;
+        }
         KSA_STEP_FENCE();
     }
-    bool raise = false;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        mx_out[qb] = mx[qb];
-        raise |= mx[qb] > st.m_ref[qb] + raise_margin;   // (mx - m_ref) * sl > threshold
-    }
-    return __builtin_amdgcn_ballot_w64(raise) != 0;
+    return raise_any;
 }
 
 // What a wave does in place of a sub-tile of a masked stretch when none of its rows sees a key of the block it would
@@ -875,35 +884,53 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 sync.kg = kbase, sync.vg = vtbase, sync.k_dst = k_wave, sync.v_dst = v_wave;
                 // does some row of this wave see a key of the tile that starts at key k0?
                 auto wave_sees = [&](int k0) { return k0 < whi && k0 + BN > wlo; };
+                // Global addresses of tile min(t, n_tiles - 1) for the request two tiles ahead (past the end of the run the
+                // last tile is requested again, into a free buffer).  Runs whose tiles all start at the same phase of the
+                // chunk pattern advance by a constant number of augmented rows per tile.
+                // (straight-line scalar code on purpose: it is executed inside a sub-tile's MFMA slot, see subtile(); the
+                // scheduler only marks items pipelined whose chunk length and summary count are powers of two, so the row
+                // of a compact index is two shifts, a multiply and two adds)
+                const int r_sh = space == KSA_SPACE_TEXT ? a.c_shift : a.m_shift;
+                const int r_msk = period - 1, r_add = space == KSA_SPACE_TEXT ? 0 : a.c;
+                auto aim = [&](int t) {
+                    const int tt = t < n_tiles ? t : n_tiles - 1;
+                    const int u = seg_begin + tt * BN;
+                    const int row = (u >> r_sh) * a.w + (u & r_msk) + r_add;
+                    sync.kg = kbase + (int64_t)row * a.ks[1];
+                    sync.vg = vtbase + tt * BN;
+                };
                 auto stretch = [&](auto masked_tag, int tn_begin, int tn_end) {
                     constexpr bool MASKED = decltype(masked_tag)::value;
                     for (int tn = tn_begin; tn < tn_end; ++tn) {
                         const int key0 = seg_begin + tn * BN;
+                        // what the first sub-tile of tile tn requests (tile tn + 2) and where it goes: b_ld after the
+                        // rotation below, i.e. the buffer tile tn - 1 leaves
+                        auto prepare_request = [&]() {
+                            aim(tn + 2);
+                            sync.k_dst = k_wave + (tn > 0 ? b_cur : b_ld);
+                            sync.v_dst = v_wave + (tn > 0 ? b_cur : b_ld);
+                        };
                         if (tn > 0) {
                             // ---- second sub-tile of tile tn-1: weights from sv_b, scores of the first half of tile tn into
                             // sv_a (for tn = n_tiles they come from a buffer that holds no new tile and are never used)
                             if (MASKED && !wave_sees(key0 - BN) && !wave_sees(key0)) {
                                 idle_subtile<D, false>(lds, ll, sv_a, ka_pre, K0 + b_nxt + HALF, mxl, sync);
+                                prepare_request();
                                 raise = false;
                             } else {
                                 if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                                 raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur,
                                                                   1, K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl,
-                                                                  sync, key0, vis_lo, vis_span) &&
+                                                                  sync, key0, vis_lo, vis_span, prepare_request) &&
                                         (tn < n_tiles);
                             }
                             const int b_old = b_cur;
                             b_cur = b_nxt, b_nxt = b_ld, b_ld = b_old;
+                        } else {
+                            prepare_request();
                         }
                         if (tn < n_tiles) {
                             // (no wait for the loads of tile tn+1 here: they get until the barrier inside the sub-tile)
-                            // the tile after next; past the end of the run the last tile is requested again (into a free
-                            // buffer)
-                            const int t_ld = tn + 2 < n_tiles ? tn + 2 : n_tiles - 1;
-                            sync.kg = kbase + tile_base(t_ld);
-                            sync.vg = vtbase + t_ld * BN;
-                            sync.k_dst = k_wave + b_ld;
-                            sync.v_dst = v_wave + b_ld;
                             // ---- first sub-tile of tile tn: weights from sv_a, scores of its second half into sv_b ----
                             if (MASKED && !wave_sees(key0)) {
                                 idle_subtile<D, true>(lds, ll, sv_b, ka_pre, K0 + b_nxt, mxl, sync);
@@ -912,7 +939,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                                 if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
                                 raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF,
                                                                  V0 + b_cur, 0, K0 + b_nxt, oacc, st, ind, sl, raise_margin,
-                                                                 mxl, sync, key0 + 32, vis_lo, vis_span);
+                                                                 mxl, sync, key0 + 32, vis_lo, vis_span, [] {});
                             }
                         }
                     }
