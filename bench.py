@@ -208,17 +208,17 @@ def main():
         print(json.dumps(res), flush=True)
         return
 
-    if args.backward_only:
-        prefill()
-        print(json.dumps({"prefill_backward": prefill_backward(cfg, lay, q, k, v, o, lse, max(args.steps, 1))}), flush=True)
-        return
-
     if args.traffic_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
         dst.copy_(src)          # 1 GiB read + 1 GiB written by one copy kernel
         torch.cuda.synchronize()
         del src, dst
+    if args.backward_only:
+        prefill()
+        print(json.dumps({"prefill_backward": prefill_backward(cfg, lay, q, k, v, o, lse, max(args.steps, 1))}), flush=True)
+        return
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
