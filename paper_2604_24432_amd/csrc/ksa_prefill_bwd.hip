@@ -132,7 +132,8 @@ __device__ __forceinline__ bf16x8 read_cols(const unsigned char *lds, int tile_c
 // acc += A B for an accumulator that lives across the whole tile loop.  Inline assembly pins it to accumulation
 // registers: left to the compiler, the 128 registers of such accumulators are copied to VGPRs and back around every
 // tile.  The compiler does not know this is an MFMA and inserts none of the wait states an MFMA needs after a VALU
-// write of its operands (the s_nop) or before a VALU read of its result (see accumulators_settle()).
+// write of its operands (the s_nop: the compiler packs the bf16 weights right in front of the statement, and without
+// it the results are wrong) or before a VALU read of its result (see accumulators_settle()).
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 &a_op, const bf16x8 &b_op) {
     asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a_op), "v"(b_op));
 }
@@ -226,7 +227,20 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
 
     const KsaWgEntry ent = a.entries[blockIdx.x];
     if (ent.item < 0) return;
-    const KsaWorkItem &item = a.items[ent.item];
+    // The item's few words are copied into scalar registers here: read through a reference inside the tile loop they
+    // would be fetched from memory again after every tile request (the requests are opaque memory operations to the
+    // compiler), each fetch followed by a wait for ALL outstanding loads, the tile in flight included.
+    const KsaWorkItem *item_p = a.items + ent.item;
+    const int n_seg = item_p->n_seg;
+    int seg_space[KSA_MAX_SEGMENTS], seg_begin[KSA_MAX_SEGMENTS], seg_end[KSA_MAX_SEGMENTS];
+    int seg_full_lo[KSA_MAX_SEGMENTS], seg_full_hi[KSA_MAX_SEGMENTS];
+    static_assert(KSA_MAX_SEGMENTS == 2, "segment fields are selected with one compare");
+#pragma unroll
+    for (int x = 0; x < KSA_MAX_SEGMENTS; ++x) {
+        seg_space[x] = item_p->seg[x].space, seg_begin[x] = item_p->seg[x].begin, seg_end[x] = item_p->seg[x].end;
+        seg_full_lo[x] = item_p->seg[x].full_lo, seg_full_hi[x] = item_p->seg[x].full_hi;
+    }
+#define KSA_SEG(field, sg) ((sg) == 0 ? field[0] : field[1])
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // as in the forward kernel: wave w takes query head w % stack and row block w / stack of the query tile
@@ -234,7 +248,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     const int wrow = wave >> a.stack_shift;
     const int r = lane & 31, h = lane >> 5;
     const LaneLds ll = lane_lds<D>(lane);
-    const int q_space = item.q_space, q_begin = item.q_begin, q_end = item.q_begin + item.q_count;
+    const int q_space = item_p->q_space, q_begin = item_p->q_begin, q_end = item_p->q_begin + item_p->q_count;
 
     int q_aug[QB];
     bool q_valid[QB];
@@ -271,21 +285,24 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
 
     // The key tiles of all runs form one sequence; tile t sits in LDS buffer t % 2 and tile t + 1 is requested right
     // after the barrier that publishes tile t, so its latency hides behind the math of tile t.
-    int seg = 0, kt = item.n_seg > 0 ? item.seg[0].begin : 0;
+    int seg = 0, kt = n_seg > 0 ? seg_begin[0] : 0;
     auto skip_empty_runs = [&]() {
-        while (seg < item.n_seg && kt >= item.seg[seg].end) {
+        while (seg < n_seg && kt >= KSA_SEG(seg_end, seg)) {
             ++seg;
-            if (seg < item.n_seg) kt = item.seg[seg].begin;
+            if (seg < n_seg) kt = KSA_SEG(seg_begin, seg);
         }
     };
     auto request = [&](int sg, int key0, int buf) {
-        const int space = item.seg[sg].space, last = item.seg[sg].end - 1;
+        const int space = KSA_SEG(seg_space, sg), last = KSA_SEG(seg_end, sg) - 1;
         load_tile_pair<D>(a, kbase, a.ks[1], vbase, a.ks[1], space, key0, last, lds + buf * 2 * BYTES,
                           lds + buf * 2 * BYTES + BYTES, wave, lane);
     };
     skip_empty_runs();
     int buf = 0;
-    if (seg < item.n_seg) request(seg, kt, 0);
+    // the wave's own rows and statistics have arrived before the first tile request: from here on only tile requests
+    // are outstanding, and the waits in the loop count those alone
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (seg < n_seg) request(seg, kt, 0);
     int elo[QB], espan[QB], range_seg = -1;
     // One tile: publish it, request the next one, compute.  MASKED tiles clip every score to its row's visible range;
     // tiles the schedule marks as seen whole by every row of the query tile do not.  The two variants are separate
@@ -296,18 +313,18 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
         const int cur_seg = seg, cur_kt = kt;
         kt += BN;
         skip_empty_runs();
-        if (seg < item.n_seg) request(seg, kt, buf ^ 1);
+        if (seg < n_seg) request(seg, kt, buf ^ 1);
         const int k_rows = buf * 2 * BYTES + ll.rows, v_rows = k_rows + BYTES, k_cols = buf * 2 * BYTES + ll.cols;
         buf ^= 1;
         if (range_seg != cur_seg) {
             range_seg = cur_seg;
-            const int space = item.seg[cur_seg].space, seg_begin = item.seg[cur_seg].begin, seg_end = item.seg[cur_seg].end;
+            const int space = KSA_SEG(seg_space, cur_seg), run_begin = KSA_SEG(seg_begin, cur_seg), run_end = KSA_SEG(seg_end, cur_seg);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 int lo, hi;
                 visible_range(a, q_space, idc[qb], space, lo, hi);
-                elo[qb] = lo > seg_begin ? lo : seg_begin;
-                const int ehi = hi < seg_end ? hi : seg_end;
+                elo[qb] = lo > run_begin ? lo : run_begin;
+                const int ehi = hi < run_end ? hi : run_end;
                 espan[qb] = ehi > elo[qb] ? ehi - elo[qb] : 0;
                 if (!q_valid[qb]) elo[qb] = 0x7fffffff, espan[qb] = 0;
             }
@@ -408,16 +425,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
             for (int j = 0; j < 2 * DB; ++j) dq_step(1, j, kt1[j]);
             KSA_FENCE();
     };
-    auto tile_is_full = [&]() { return kt >= item.seg[seg].full_lo && kt + BN <= item.seg[seg].full_hi; };
-    while (seg < item.n_seg) {
+    auto tile_is_full = [&]() { return kt >= KSA_SEG(seg_full_lo, seg) && kt + BN <= KSA_SEG(seg_full_hi, seg); };
+    while (seg < n_seg) {
         if (tile_is_full()) {
             do step(std::false_type{});
-            while (seg < item.n_seg && tile_is_full());
+            while (seg < n_seg && tile_is_full());
         } else {
             do step(std::true_type{});
-            while (seg < item.n_seg && !tile_is_full());
+            while (seg < n_seg && !tile_is_full());
         }
     }
+#undef KSA_SEG
 
     accumulators_settle();
 #pragma unroll
@@ -437,7 +455,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
 }
 
 // ---- dK, dV -------------------------------------------------------------------------------------------------
-template <int D>
+// POW2: chunk_len and n_summary are powers of two, so that the row maps are shifts and the bookkeeping of the next
+// tile request is short straight-line code that can sit between the MFMAs of the tile in work.  Otherwise the same
+// statements run in one block after the barrier.
+template <int D, bool POW2>
 __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     constexpr int KS = D / 16, DB = D / 32, BYTES = BN * D * 2;
     // tiles in flight + 1: the query tiles of a long run stream from HBM (their total is far beyond the caches), and
@@ -487,9 +508,9 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // The query rows that can see a key of [k0, k1): one run of text rows, one of summary rows (supersets: every
     // score is masked below).  Text keys of chunks jl..jh are seen by the text rows from k0 to the end of chunk
     // jh + C and by the summary rows of chunks jl..jh; summary keys of chunks jl..jh by the text rows from chunk
-    // jl + C + 1 on and by the summary rows of their own chunks from k0 on.
-    int run_space[2], run_begin[2], run_end[2];
-    run_space[0] = KSA_SPACE_TEXT, run_space[1] = KSA_SPACE_SUMMARY;
+    // jl + C + 1 on and by the summary rows of their own chunks from k0 on.  Run x is in index space x.
+    static_assert(KSA_SPACE_TEXT == 0 && KSA_SPACE_SUMMARY == 1, "a run's number is its index space");
+    int run_begin[2], run_end[2];
     if (space == KSA_SPACE_TEXT) {
         const int jl = div_by(k0, a.c, a.c_shift), jh = div_by(k1 - 1, a.c, a.c_shift);
         const int64_t te = ((int64_t)jh + a.C + 1) * a.c;
@@ -509,209 +530,318 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // blocks of the index space that overlap it, from the LAST one downwards (every key tile of a head then meets the
     // same query tiles in the same order, whatever its own first row is), the heads of the group innermost.  Rows
     // of a block outside the run are masked through their visible range.  Tile t of the sequence sits in LDS stage
-    // t % STAGES with its row statistics; tile t + STAGES - 1 is requested right after the barrier that publishes
-    // tile t.
+    // t % STAGES with its row statistics.
     int run_first_blk[2], run_tiles[2];
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
         run_first_blk[x] = run_begin[x] / BN;
         run_tiles[x] = run_end[x] > run_begin[x] ? (run_end[x] - 1) / BN - run_first_blk[x] + 1 : 0;
     }
-    int run = 0, ti = 0, hj = 0;   // the next tile to request
-    auto skip_empty_runs = [&]() {
-        while (run < 2 && ti >= run_tiles[run]) ++run, ti = 0;
-    };
-    // Requests the next tile of the sequence into `stage`: every wave issues LOADS_PER_TILE loads, so that the waits
-    // below can count them.
-    constexpr int LOADS_PER_TILE = 2 * (RW / (64 / (D / 8))) + 2;
-    const int stats_stride = a.nt_pad + a.ns_pad;
-    unsigned full_mask = 0;   // bit `stage`: every row of the tile in that stage sees every key of the workgroup
-    auto request = [&](int stage) {
-        const int head = hkv * a.group + hj, q_space = run_space[run];
-        const int first = (run_first_blk[run] + run_tiles[run] - 1 - ti) * BN;
-        const __bf16 *qbase = a.q + b * a.qs[0] + head * a.qs[2];
-        const __bf16 *gbase = a.g + b * a.os[0] + head * a.os[2];
-        unsigned char *q_tile = lds + stage * 2 * BYTES, *g_tile = q_tile + BYTES;
-        const bool whole = first >= run_begin[run] && first + BN <= run_end[run];   // no row of the block outside the run
-        load_tile_pair<D>(a, qbase, a.qs[1], gbase, a.os[1], q_space, first, run_end[run] - 1, q_tile, g_tile, wave, lane);
-        // lse and delta of the 64 rows: one 4-byte piece per lane, straight into LDS (all waves fetch the same 256
-        // bytes: keeps the per-wave load count uniform, and costs nothing)
-        const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (q_space == KSA_SPACE_TEXT ? 0 : a.nt_pad) +
-                           first + lane;
-        lds_direct_load_4(a.lse2c + at, reinterpret_cast<const unsigned char *>(&st_lse[stage][0]));
-        lds_direct_load_4(a.dlc + at, reinterpret_cast<const unsigned char *>(&st_dl[stage][0]));
-        // Visible ranges are monotone in the row index (Eq. 3: both ends of a row's range never move backwards from one
-        // row to the next), so the block is seen whole iff its last row's range starts at or before the first key and
-        // its first row's range ends at or behind the last key: two scalar evaluations, no per-row work.
-        bool full = false;
-        if (whole) {
-            int lo_f, hi_f, lo_l, hi_l;
-            visible_range(a, q_space, first, space, lo_f, hi_f);
-            visible_range(a, q_space, first + BN - 1, space, lo_l, hi_l);
-            full = lo_l <= k0 && hi_f >= k1;
+    const int n_tiles = (run_tiles[0] + run_tiles[1]) * a.group;   // > 0: a key is seen by its own row at least
+    // Blocks [full_lo_blk, full_hi_blk) of a run (counted from the run's first block) are seen whole: no row of such
+    // a block lies outside the run, and every row sees every key of the workgroup.  Visible ranges are monotone in
+    // the row index (Eq. 3: both ends of a row's range never move backwards from one row to the next), so these
+    // blocks are consecutive: the first block whose first row's range ends at or behind the last key, up to the last
+    // block whose last row's range starts at or before the first key.  Two bisections per run, once per workgroup;
+    // the tile loop then only compares block numbers.
+    int full_lo_blk[2], full_hi_blk[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const int w_lo = run_begin[x] % BN == 0 ? 0 : 1;                       // blocks without rows outside the run
+        const int w_hi = run_tiles[x] - (run_end[x] % BN == 0 ? 0 : 1);
+        int lo_b = w_lo, hi_b = w_hi > w_lo ? w_hi : w_lo;   // first block in [w_lo, w_hi) whose first row sees key k1 - 1
+        while (lo_b < hi_b) {
+            const int mid = (lo_b + hi_b) >> 1;
+            int rlo, rhi;
+            visible_range(a, x, (run_first_blk[x] + mid) * BN, space, rlo, rhi);
+            if (rhi >= k1) hi_b = mid; else lo_b = mid + 1;
         }
-        full_mask = (full_mask & ~(1u << stage)) | ((full ? 1u : 0u) << stage);
-        if (!full && tid < BN) {   // visible key range of each row (empty for rows of the block outside the run)
-            const int qi = first + tid;
+        full_lo_blk[x] = lo_b;
+        lo_b = w_lo, hi_b = w_hi > w_lo ? w_hi : w_lo;        // first block in [w_lo, w_hi) whose last row no longer sees key k0
+        while (lo_b < hi_b) {
+            const int mid = (lo_b + hi_b) >> 1;
+            int rlo, rhi;
+            visible_range(a, x, (run_first_blk[x] + mid) * BN + BN - 1, space, rlo, rhi);
+            if (rlo > k0) hi_b = mid; else lo_b = mid + 1;
+        }
+        full_hi_blk[x] = lo_b;
+    }
+#define KSA_RUN(field, x) ((x) == 0 ? field[0] : field[1])
+
+    // ---- the request of a tile, in two parts ----------------------------------------------------------------
+    // prepare: advances the sequence and works out where the tile's rows are (scalar tile data, one offset per lane
+    //          and load instruction); issue: the LOADS_PER_TILE global -> LDS loads of a wave.  The two are separate
+    //          so that each can be dealt into the MFMA stream of the tile in work: the loads go out one behind each
+    //          of the first MFMAs of a step (a load instruction occupies the issue port for tens of cycles), the
+    //          arithmetic of the following request runs behind the last ones.  When the sequence is exhausted,
+    //          prepare leaves the last tile in place and the loads fetch it again into a stage nobody reads: every
+    //          step then issues the same number of loads, which is what the counted waits rely on.
+    constexpr int CH = D / 8, RPI = 64 / CH, NI = RW / RPI;
+    constexpr int LOADS_PER_TILE = 2 * NI + 2;
+    static_assert(RW % RPI == 0 && NI >= 1, "a wave's share of a tile is a whole number of load instructions");
+    static_assert(LOADS_PER_TILE <= 2 * KS, "one load behind each MFMA of the first score block");
+    const int stats_stride = a.nt_pad + a.ns_pad;
+    const unsigned q_row_bytes = (unsigned)a.qs[1] * 2u, g_row_bytes = (unsigned)a.os[1] * 2u;
+    // the next tile of the sequence; stays on the last tile once the sequence is exhausted
+    int sq_run = run_tiles[0] > 0 ? 0 : 1, sq_ti = 0, sq_hj = 0;
+    struct Request {
+        const __bf16 *q_base, *g_base;   // row `first` of the tile (scalar)
+        const float *lse_p, *dl_p;       // statistics of row `first` (scalar)
+        unsigned q_off[NI], g_off[NI];   // per lane: byte offset of the 16 bytes it fetches, per load instruction
+        int q_space, first;
+        bool full;                       // every row of the tile sees every key of the workgroup
+    } rq;
+    rq.q_base = a.q, rq.g_base = a.g, rq.lse_p = a.lse2c, rq.dl_p = a.dlc, rq.q_space = 0, rq.first = 0, rq.full = false;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) rq.q_off[i] = rq.g_off[i] = 0;
+    // compact index -> chunk number and augmented row, in index space sp (scalar sp)
+    auto chunk_of = [&](int sp, int idx) {
+        if constexpr (POW2) return idx >> (sp == KSA_SPACE_TEXT ? a.c_shift : a.m_shift);
+        return idx / (sp == KSA_SPACE_TEXT ? a.c : a.m);
+    };
+    auto prepare_tile = [&]() {   // scalar part
+        const int run = sq_run, cur_ti = sq_ti;
+        const int first = (KSA_RUN(run_first_blk, run) + KSA_RUN(run_tiles, run) - 1 - sq_ti) * BN;
+        const int head = hkv * a.group + sq_hj;
+        {   // advance, unless this is the last tile
+            int hj = sq_hj + 1, ti = sq_ti, rn = sq_run;
+            const bool wrap = hj == a.group;
+            hj = wrap ? 0 : hj, ti = wrap ? ti + 1 : ti;
+            const bool run_done = ti >= KSA_RUN(run_tiles, rn);
+            rn = run_done ? rn + 1 : rn, ti = run_done ? 0 : ti;
+            const bool more = rn < 2 && (rn == 0 || run_tiles[1] > 0);
+            sq_hj = more ? hj : sq_hj, sq_ti = more ? ti : sq_ti, sq_run = more ? rn : sq_run;
+        }
+        const int per = run == KSA_SPACE_TEXT ? a.m : a.c;   // rows of the other kind per chunk
+        const int add = run == KSA_SPACE_TEXT ? 0 : a.c;
+        const int64_t arow = (int64_t)first + (int64_t)chunk_of(run, first) * per + add;
+        rq.q_base = a.q + b * a.qs[0] + head * a.qs[2] + arow * a.qs[1];
+        rq.g_base = a.g + b * a.os[0] + head * a.os[2] + arow * a.os[1];
+        const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (run == KSA_SPACE_TEXT ? 0 : a.nt_pad) + first;
+        rq.lse_p = a.lse2c + at, rq.dl_p = a.dlc + at;
+        rq.q_space = run, rq.first = first;
+        const int bi = KSA_RUN(run_tiles, run) - 1 - cur_ti;
+        rq.full = bi >= KSA_RUN(full_lo_blk, run) && bi < KSA_RUN(full_hi_blk, run);
+    };
+    auto prepare_row = [&](int i) {   // per-lane part of load instruction i
+        const int run = rq.q_space, first = rq.first;
+        const int row = RW * wave + RPI * i + lane / CH;
+        int idx = first + row;
+        const int last = KSA_RUN(run_end, run) - 1;
+        idx = idx < last ? idx : last;
+        const int per = run == KSA_SPACE_TEXT ? a.m : a.c;
+        // augmented row of idx minus that of `first`: the index distance plus the other kind's rows in between
+        const int d_rows = (idx - first) + (chunk_of(run, idx) - chunk_of(run, first)) * per;
+        const unsigned col = (unsigned)(((lane % CH) ^ swz<D>(row)) << 4);
+        rq.q_off[i] = (unsigned)d_rows * q_row_bytes + col;
+        rq.g_off[i] = (unsigned)d_rows * g_row_bytes + col;
+    };
+    auto prepare_all = [&]() {
+        prepare_tile();
+#pragma unroll
+        for (int i = 0; i < NI; ++i) prepare_row(i);
+    };
+    const unsigned lds_tiles = (unsigned)(size_t)lds, lds_lse = (unsigned)(size_t)&st_lse[0][0], lds_dl = (unsigned)(size_t)&st_dl[0][0];
+    // load instruction x of the prepared tile into `stage`: x < 2 NI the tile rows, then the two statistics rows
+    // (lse and delta of the 64 rows, one 4-byte piece per lane; all waves fetch the same 256 bytes, which keeps the
+    // per-wave load count uniform and costs nothing)
+    auto issue_load = [&](int stage, int x) {
+        if (x < 2 * NI) {
+            const int i = x / 2;
+            const unsigned dst = lds_tiles + (unsigned)stage * 2 * BYTES + (x % 2) * BYTES + (RW * wave + RPI * i) * (D * 2);
+            if (x % 2 == 0)
+                lds_direct_load_16_s(rq.q_base, rq.q_off[i], __builtin_amdgcn_readfirstlane(dst));
+            else
+                lds_direct_load_16_s(rq.g_base, rq.g_off[i], __builtin_amdgcn_readfirstlane(dst));
+        } else {
+            const float *src = (x == 2 * NI ? rq.lse_p : rq.dl_p) + lane;
+            lds_direct_load_4(src, reinterpret_cast<const unsigned char *>((size_t)((x == 2 * NI ? lds_lse : lds_dl) + (unsigned)stage * BN * 4)));
+        }
+    };
+    unsigned full_mask = 0;   // bit `stage`: every row of the tile in that stage sees every key of the workgroup
+    // what goes with the loads of a tile: the full flag of its stage and, unless the tile is seen whole, the visible
+    // key range of each row (empty for rows of the block outside the run)
+    auto issue_flags = [&](int stage) {
+        full_mask = (full_mask & ~(1u << stage)) | ((rq.full ? 1u : 0u) << stage);
+        if (!rq.full && tid < BN) {
+            const int qi = rq.first + tid, run = rq.q_space;
             int lo = 0x7fffffff, hi = 0;
-            if (qi >= run_begin[run] && qi < run_end[run]) visible_range(a, q_space, qi, space, lo, hi);
+            if (qi >= KSA_RUN(run_begin, run) && qi < KSA_RUN(run_end, run)) visible_range(a, run, qi, space, lo, hi);
             st_lo[stage][tid] = lo, st_span[stage][tid] = hi > lo ? hi - lo : 0;
         }
-        if (++hj == a.group) hj = 0, ++ti;
-        skip_empty_runs();
     };
-    skip_empty_runs();
-    int pending = 0;   // tiles requested and not yet consumed
-    for (; pending < STAGES - 1 && run < 2; ++pending) request(pending);
-    int buf = 0;       // stage of the oldest pending tile
-    // One tile: publish it, request the tile STAGES - 1 ahead, compute.  The tile's two 32-row blocks are two streams,
-    // each scores -> weights -> gradients, interleaved by hand (one wave per SIMD has nobody else to fill the matrix
-    // pipe while its VALU block runs): the weights of block 0 are computed in four chunks with the score MFMAs of
-    // block 1 dealt between them, the weights of block 1 with the gradient MFMAs of block 0.  Source order is the
-    // intended issue order, pinned with scheduling fences; LDS operands and row statistics are read one step ahead of
-    // their use.  A tile all of whose rows see all of the workgroup's keys (nearly every tile of a summary key) skips
-    // the visibility test: the two variants are separate instantiations walked in stretches.
+
+    // The wave's own K and V rows have arrived before the first tile request: from here on only tile requests are
+    // outstanding, which is what the counted waits of the loop assume.  (Left to the compiler, the wait for these rows
+    // sits in front of their first use inside the loop, where it also waits for every tile in flight.)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    // tiles 0 .. STAGES - 2 are requested up front; the request of tile STAGES - 1 is prepared for step 0
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st) {
+        prepare_all();
+        issue_flags(st);
+#pragma unroll
+        for (int x = 0; x < LOADS_PER_TILE; ++x) issue_load(st, x);
+    }
+    prepare_all();
+    int buf = 0;   // stage of the tile in work
+
+    // One tile: publish it, request the tile STAGES - 1 ahead, compute.  The tile's work is a stream of 4 KS pairs of
+    // MFMAs -- scores of row block 0, scores of row block 1, gradient products of block 0, of block 1 -- and one wave
+    // per SIMD has nobody else to fill the matrix pipe while its other instructions issue, so everything else is
+    // dealt into that stream by hand: the loads of the next request behind the MFMAs of the first block's scores, the
+    // weights of block 0 (one pair of query rows per MFMA) behind the scores of block 1, those of block 1 behind the
+    // gradient products of block 0, the arithmetic of the request after next behind the gradient products of block 1.
+    // An MFMA executes for 8 passes while the wave goes on issuing, so the pieces between two MFMAs have to stay
+    // short.  Source order is the intended issue order, pinned with scheduling fences; LDS operands are read AHEAD
+    // pairs before the MFMAs that consume them.  A tile all of whose rows see all of the workgroup's keys (nearly
+    // every tile of a summary key) skips the visibility test: the two variants are separate instantiations walked in
+    // stretches.
     auto step = [&](auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        // the oldest pending tile is complete when at most the loads of the younger ones are outstanding
-        if (pending >= 3)
-            __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LOADS_PER_TILE) & 15) | (((2 * LOADS_PER_TILE) >> 4) << 14));
-        else if (pending == 2)
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (LOADS_PER_TILE & 15) | ((LOADS_PER_TILE >> 4) << 14));
-        else
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+        // the tile in work is complete when at most the loads of the two younger ones are outstanding
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LOADS_PER_TILE) & 15) | (((2 * LOADS_PER_TILE) >> 4) << 14));
         __syncthreads();   // that tile is published; everybody is done with the stage the next request overwrites
-        if (run < 2)
-            request((buf + STAGES - 1) % STAGES);
-        else
-            --pending;
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
-        constexpr int NC = 4;               // chunks of a block's VALU work: four query rows per lane each
-        constexpr int SPC = KS / NC;        // score k steps dealt into one chunk
-        constexpr int PPC = 2 * DB / NC;    // gradient (16-row group, 32-column block) pairs dealt into one chunk
-        static_assert(KS % NC == 0 && (2 * DB) % NC == 0, "the MFMAs of a block are dealt evenly over the chunks");
+        const int req_stage = (buf + STAGES - 1) % STAGES;
+        static_assert(2 * DB == KS, "a block's gradient products are as many MFMA pairs as its score steps");
+        constexpr int NP = 4 * KS;      // MFMA pairs of a tile
+        constexpr int AHEAD = 3;        // operand reads run this many pairs ahead
+        constexpr int WPP = 8 / KS;     // weights (of a lane's 16 query rows per block) dealt behind one MFMA
+        constexpr int STATS_AHEAD = 2;  // row statistics are read this many pairs before their first use
         f32x16 sacc[2], gacc[2];
-        bf16x8 pp[2][2], pd[2][2];          // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
-
-        struct Stats { f32x4 l4, d4; int4 lo4, span4; };
-        auto read_stats = [&](int qb, int gg) {
-            const int row0 = qb * 32 + 8 * gg + 4 * h;
-            Stats st;
-            st.l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
-            st.d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
-            if constexpr (MASKED) {
-                st.lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
-                st.span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
-            }
-            return st;
-        };
-        auto weights_chunk = [&](int qb, int gg, const Stats &cur) {
-            const int lo_e[4] = {cur.lo4.x, cur.lo4.y, cur.lo4.z, cur.lo4.w};
-            const int span_e[4] = {cur.span4.x, cur.span4.y, cur.span4.z, cur.span4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int g = gg * 4 + e;
-                float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -cur.l4[e]));
-                // one subtraction and one unsigned compare: lo <= key < lo + span
-                if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
-                pp[qb][g / 8][g % 8] = (__bf16)p;
-                pd[qb][g / 8][g % 8] = (__bf16)(p * (gacc[qb][g] - cur.d4[e]));
-            }
-        };
-        auto score_step = [&](int qb, int s, const bf16x8 &q_op, const bf16x8 &g_op) {
-            if (s == 0) {
-                mfma_score<true>(sacc[qb], q_op, kreg[0]);
-                mfma_score<true>(gacc[qb], g_op, vreg[0]);
+        bf16x8 pp[2][2], pd[2][2];      // P and dS in the B-operand layout: lane = key, eight registers = eight query rows
+        bf16x8 op_q[NP], op_g[NP];      // pair i: rows of Q / G (scores) or columns of Q / G (gradient products)
+        auto read_ops = [&](int i) {
+            const int ph = i / KS, x = i % KS;
+            if (ph < 2) {
+                op_q[i] = read_rows<D>(lds, q_rows, ph, x), op_g[i] = read_rows<D>(lds, g_rows, ph, x);
             } else {
-                mfma_score<false>(sacc[qb], q_op, kreg[s]);
-                mfma_score<false>(gacc[qb], g_op, vreg[s]);
+                op_g[i] = read_cols<D>(lds, g_cols, (ph - 2) * 32 + (x / DB) * 16, x % DB);
+                op_q[i] = read_cols<D>(lds, q_cols, (ph - 2) * 32 + (x / DB) * 16, x % DB);
             }
         };
-        // dV^T += G^T P, dK^T += Q^T dS for the pair j = (16-row group hf, 32-column block db) of query block qb
-        auto grad_step = [&](int qb, int j, const bf16x8 &gt_op, const bf16x8 &qt_op) {
-            mfma_acc(dvacc[j % DB], gt_op, pp[qb][j / DB]);
-            mfma_acc(dkacc[j % DB], qt_op, pd[qb][j / DB]);
-        };
-        auto read_pair = [&](int qb, int j, bf16x8 &gt_op, bf16x8 &qt_op) {
-            gt_op = read_cols<D>(lds, g_cols, qb * 32 + (j / DB) * 16, j % DB);
-            qt_op = read_cols<D>(lds, q_cols, qb * 32 + (j / DB) * 16, j % DB);
-        };
-
-        // ---- scores of block 0 (alone on the matrix pipe)
-        {
-            bf16x8 qa[KS], ga[KS];
 #pragma unroll
-            for (int s = 0; s < KS; ++s) qa[s] = read_rows<D>(lds, q_rows, 0, s), ga[s] = read_rows<D>(lds, g_rows, 0, s);
-            KSA_FENCE();
+        for (int i = 0; i < AHEAD; ++i) read_ops(i);
+        issue_flags(req_stage);
+        if constexpr (!POW2) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) score_step(0, s, qa[s], ga[s]);
-            KSA_FENCE();
-        }
-        // ---- weights of block 0 between the scores of block 1
-        {
-            bf16x8 qa[KS], ga[KS];
-            qa[0] = read_rows<D>(lds, q_rows, 1, 0), ga[0] = read_rows<D>(lds, g_rows, 1, 0);
-            Stats nxt = read_stats(0, 0);
-            scores_settle();
-            KSA_FENCE();
-#pragma unroll
-            for (int gg = 0; gg < NC; ++gg) {
-                const Stats cur = nxt;
-                if (gg + 1 < NC) nxt = read_stats(0, gg + 1);
-#pragma unroll
-                for (int x = 0; x < SPC; ++x) {
-                    const int s = gg * SPC + x;
-                    if (s + 1 < KS) qa[s + 1] = read_rows<D>(lds, q_rows, 1, s + 1), ga[s + 1] = read_rows<D>(lds, g_rows, 1, s + 1);
-                    score_step(1, s, qa[s], ga[s]);
-                }
-                weights_chunk(0, gg, cur);
-                KSA_FENCE();
-            }
-        }
-        // ---- weights of block 1 between the gradient products of block 0
-        bf16x8 gt1[2 * DB], qt1[2 * DB];
-        {
-            bf16x8 gt0[2 * DB], qt0[2 * DB];
-            read_pair(0, 0, gt0[0], qt0[0]);
-            Stats nxt = read_stats(1, 0);
-            scores_settle();
-            KSA_FENCE();
-#pragma unroll
-            for (int gg = 0; gg < NC; ++gg) {
-                const Stats cur = nxt;
-                if (gg + 1 < NC) nxt = read_stats(1, gg + 1);
-#pragma unroll
-                for (int x = 0; x < PPC; ++x) {
-                    const int j = gg * PPC + x;
-                    if (j + 1 < 2 * DB) read_pair(0, j + 1, gt0[j + 1], qt0[j + 1]);
-                    grad_step(0, j, gt0[j], qt0[j]);
-                }
-                weights_chunk(1, gg, cur);
-                if (gg == NC - 1) read_pair(1, 0, gt1[0], qt1[0]);
-                KSA_FENCE();
-            }
-        }
-        // ---- gradient products of block 1 (alone on the matrix pipe)
-#pragma unroll
-        for (int j = 0; j < 2 * DB; ++j) {
-            if (j + 1 < 2 * DB) read_pair(1, j + 1, gt1[j + 1], qt1[j + 1]);
-            grad_step(1, j, gt1[j], qt1[j]);
+            for (int x = 0; x < LOADS_PER_TILE; ++x) issue_load(req_stage, x);
+            prepare_all();
         }
         KSA_FENCE();
+
+        // statistics of rows 8 gg + 4 h .. + 3 of block qb: the rows of a lane's score registers 4 gg .. 4 gg + 3
+        struct Stats { f32x4 l4, d4; int4 lo4, span4; };
+        Stats stats[2][4];
+        auto read_stats = [&](int qb, int gg) {
+            const int row0 = qb * 32 + 8 * gg + 4 * h;
+            stats[qb][gg].l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
+            stats[qb][gg].d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
+            if constexpr (MASKED) {
+                stats[qb][gg].lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
+                stats[qb][gg].span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
+            }
+        };
+        // weights of score register g of block qb (one query row of the lane's key); the bf16 pair is packed when
+        // its second member is done
+        float pf[2][16], df[2][16];
+        auto weight = [&](int qb, int g) {
+            const Stats &cur = stats[qb][g / 4];
+            const int lo_e[4] = {cur.lo4.x, cur.lo4.y, cur.lo4.z, cur.lo4.w};
+            const int span_e[4] = {cur.span4.x, cur.span4.y, cur.span4.z, cur.span4.w};
+            const int e = g % 4;
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][g], sl, -cur.l4[e]));
+            // one subtraction and one unsigned compare: lo <= key < lo + span
+            if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
+            pf[qb][g] = p;
+            df[qb][g] = p * (gacc[qb][g] - cur.d4[e]);
+            if (g % 2 == 1) {
+                pp[qb][g / 8][g % 8 - 1] = (__bf16)pf[qb][g - 1], pp[qb][g / 8][g % 8] = (__bf16)pf[qb][g];
+                pd[qb][g / 8][g % 8 - 1] = (__bf16)df[qb][g - 1], pd[qb][g / 8][g % 8] = (__bf16)df[qb][g];
+            }
+        };
+        // first pair whose weights use the statistics group gg of block qb
+        auto first_use = [](int qb, int gg) { return (1 + qb) * KS + 4 * gg / (2 * WPP); };
+
+        // one phase of the stream (a loop of its own per phase, so that each unrolls completely)
+        auto phase = [&](auto ph_tag) {
+            constexpr int ph = decltype(ph_tag)::value;
+#pragma unroll
+            for (int x = 0; x < KS; ++x) {
+                const int i = ph * KS + x;
+                if (i + AHEAD < NP) read_ops(i + AHEAD);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int gg = 0; gg < 4; ++gg)
+                        if (i == (first_use(qb, gg) - STATS_AHEAD > 0 ? first_use(qb, gg) - STATS_AHEAD : 0)) read_stats(qb, gg);
+                // the pair's two MFMAs, each followed by its share of the other work
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int slot = 2 * x + half;   // MFMA number within the phase
+                    if constexpr (ph < 2) {
+                        f32x16 &acc = half == 0 ? sacc[ph] : gacc[ph];
+                        const bf16x8 &a_op = half == 0 ? op_q[i] : op_g[i];
+                        const bf16x8 &b_op = half == 0 ? kreg[x] : vreg[x];
+                        if (x == 0)
+                            mfma_score<true>(acc, a_op, b_op);
+                        else
+                            mfma_score<false>(acc, a_op, b_op);
+                    } else if (half == 0) {
+                        // dV^T += G^T P, dK^T += Q^T dS for (16-row group x / DB, 32-column block x % DB) of block ph - 2
+                        mfma_acc(dvacc[x % DB], op_g[i], pp[ph - 2][x / DB]);
+                    } else {
+                        mfma_acc(dkacc[x % DB], op_q[i], pd[ph - 2][x / DB]);
+                    }
+                    if constexpr (POW2 && ph == 0) {
+                        if (slot < LOADS_PER_TILE) issue_load(req_stage, slot);
+                    }
+                    if constexpr (POW2 && ph == 3) {
+                        if (slot == 0) prepare_tile();
+                        if (slot >= 1 && slot - 1 < NI) prepare_row(slot - 1);
+                    }
+                    if constexpr (ph == 1 || ph == 2) {
+                        // The scores of block ph - 1 were completed by the pair before this one.  The compiler does
+                        // not know that the statements above are MFMAs: the empty statement keeps the code that reads
+                        // those scores behind this pair's two MFMAs, which take longer to issue than the last results
+                        // need to land.  (The first MFMA's share of the weights moves behind the second one.)
+                        if (slot == 1) {
+                            asm volatile("" : "+v"(sacc[ph - 1]), "+v"(gacc[ph - 1]));
+#pragma unroll
+                            for (int y = 0; y < WPP; ++y) weight(ph - 1, y);
+                        }
+                        if (slot >= 1) {
+#pragma unroll
+                            for (int y = 0; y < WPP; ++y) weight(ph - 1, slot * WPP + y);
+                        }
+                    }
+                    KSA_FENCE();
+                }
+            }
+        };
+        phase(std::integral_constant<int, 0>{});
+        phase(std::integral_constant<int, 1>{});
+        phase(std::integral_constant<int, 2>{});
+        phase(std::integral_constant<int, 3>{});
         buf = (buf + 1) % STAGES;
     };
+#undef KSA_RUN
     auto next_is_full = [&]() { return ((full_mask >> buf) & 1u) != 0; };
-    while (pending > 0) {
+    int left = n_tiles;
+    while (left > 0) {
         if (next_is_full()) {
-            do step(std::false_type{});
-            while (pending > 0 && next_is_full());
+            do step(std::false_type{}), --left;
+            while (left > 0 && next_is_full());
         } else {
-            do step(std::true_type{});
-            while (pending > 0 && !next_is_full());
+            do step(std::true_type{}), --left;
+            while (left > 0 && !next_is_full());
         }
     }
 
+    // nothing of this workgroup is in flight any more when it leaves (the last requests fetched tiles nobody reads)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     accumulators_settle();
     if (!key_valid) return;
     __bf16 *kp = a.dk + b * a.dks[0] + (int64_t)key_aug * a.dks[1] + hkv * a.dks[2];
@@ -798,15 +928,29 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     if (delta_blocks >= ((int64_t)1 << 31) || L.p.batch > 65535 ||
         ((int64_t)a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch >= ((int64_t)1 << 31))
         return KSA_ERR_UNSUPPORTED;
+    const bool pow2 = a.c_shift >= 0 && (a.m == 0 || a.m_shift >= 0);
+    {   // the dK/dV kernel addresses the rows of a query tile by unsigned 32-bit byte offsets from the tile's first row
+        const int64_t span_text = 63 + (63 / a.c + 1) * (int64_t)a.m;
+        const int64_t span_sum = a.m > 0 ? 63 + (63 / a.m + 1) * (int64_t)a.c : 0;
+        const int64_t span = span_text > span_sum ? span_text : span_sum;
+        const int64_t row_elems = a.qs[1] > a.os[1] ? a.qs[1] : a.os[1];
+        if (a.qs[1] <= 0 || a.os[1] <= 0 || span * row_elems * 2 + 2 * L.p.head_dim >= ((int64_t)1 << 32)) return KSA_ERR_UNSUPPORTED;
+    }
     const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv((unsigned)((a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch));
     if (L.p.head_dim == 128) {
         hipLaunchKernelGGL(ksa_bwd_delta_kernel<128>, dim3((unsigned)delta_blocks), dim3(256), 0, st, a, n_rows);
         hipLaunchKernelGGL(ksa_bwd_dq_kernel<128>, grid_dq, block, 0, st, a);
-        hipLaunchKernelGGL(ksa_bwd_dkv_kernel<128>, grid_dkv, block, 0, st, a);
+        if (pow2)
+            hipLaunchKernelGGL((ksa_bwd_dkv_kernel<128, true>), grid_dkv, block, 0, st, a);
+        else
+            hipLaunchKernelGGL((ksa_bwd_dkv_kernel<128, false>), grid_dkv, block, 0, st, a);
     } else {
         hipLaunchKernelGGL(ksa_bwd_delta_kernel<64>, dim3((unsigned)delta_blocks), dim3(256), 0, st, a, n_rows);
         hipLaunchKernelGGL(ksa_bwd_dq_kernel<64>, grid_dq, block, 0, st, a);
-        hipLaunchKernelGGL(ksa_bwd_dkv_kernel<64>, grid_dkv, block, 0, st, a);
+        if (pow2)
+            hipLaunchKernelGGL((ksa_bwd_dkv_kernel<64, true>), grid_dkv, block, 0, st, a);
+        else
+            hipLaunchKernelGGL((ksa_bwd_dkv_kernel<64, false>), grid_dkv, block, 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? KSA_OK : KSA_ERR_HIP;
 }
