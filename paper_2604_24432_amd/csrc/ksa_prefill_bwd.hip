@@ -220,7 +220,10 @@ __global__ __launch_bounds__(256) void ksa_bwd_delta_kernel(const BwdArgs a, int
 }
 
 // ---- dQ -----------------------------------------------------------------------------------------------------
-template <int D>
+// POW2: chunk_len and n_summary are powers of two, so that the row maps are shifts and the bookkeeping of the next
+// tile request is short straight-line code that can sit between the MFMAs of the tile in work.  Otherwise the same
+// statements run in one block after the barrier.
+template <int D, bool POW2>
 __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     constexpr int KS = D / 16, DB = D / 32, BYTES = BN * D * 2;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * BYTES];   // two buffers of a K and a V tile
@@ -283,39 +286,125 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
     const float sl = a.scale_log2e;
 
-    // The key tiles of all runs form one sequence; tile t sits in LDS buffer t % 2 and tile t + 1 is requested right
-    // after the barrier that publishes tile t, so its latency hides behind the math of tile t.
-    int seg = 0, kt = n_seg > 0 ? seg_begin[0] : 0;
-    auto skip_empty_runs = [&]() {
-        while (seg < n_seg && kt >= KSA_SEG(seg_end, seg)) {
-            ++seg;
-            if (seg < n_seg) kt = KSA_SEG(seg_begin, seg);
+    // The key tiles of all runs form one sequence; tile t sits in LDS buffer t % 2, and the loads of tile t + 1 go out
+    // during the step of tile t, after the barrier that publishes tile t.
+    int n_tiles = 0;
+#pragma unroll
+    for (int x = 0; x < KSA_MAX_SEGMENTS; ++x)
+        if (x < n_seg && seg_end[x] > seg_begin[x]) n_tiles += (seg_end[x] - seg_begin[x] + BN - 1) / BN;
+
+    // ---- the request of a tile, in two parts (as in the dK/dV kernel) ------------------------------------------
+    // prepare: advances the sequence and works out where the tile's rows are; issue: the wave's 2 NI loads.  Once
+    // the sequence is exhausted prepare stays on the last tile, which is then fetched again into the buffer nobody
+    // reads: every step issues the same loads, and the tile loop carries no branch.
+    constexpr int CH = D / 8, RPI = 64 / CH, NI = RW / RPI;
+    static_assert(RW % RPI == 0 && NI >= 1, "a wave's share of a tile is a whole number of load instructions");
+    const unsigned kv_row_bytes = (unsigned)a.ks[1] * 2u;
+    // the next tile of the sequence (an empty first run is skipped; the host schedule has no item without tiles)
+    const int second_run = (n_seg > 1 && seg_end[1] > seg_begin[1]) ? 1 : 0;
+    int sq_seg = (n_seg > 1 && seg_end[0] <= seg_begin[0]) ? 1 : 0;
+    int sq_kt = KSA_SEG(seg_begin, sq_seg);
+    struct Request {
+        const __bf16 *k_base, *v_base;   // row `first` of the tile (scalar)
+        unsigned off[NI];                // per lane: byte offset of the 16 bytes it fetches, per load instruction
+        int seg, first;
+        bool full;                       // every row of the query tile sees every key of the tile
+    } rq;
+    rq.k_base = kbase, rq.v_base = vbase, rq.seg = 0, rq.first = 0, rq.full = false;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) rq.off[i] = 0;
+    auto chunk_of = [&](int sp, int idx) {
+        if constexpr (POW2) return idx >> (sp == KSA_SPACE_TEXT ? a.c_shift : a.m_shift);
+        return idx / (sp == KSA_SPACE_TEXT ? a.c : a.m);
+    };
+    auto prepare_tile = [&]() {   // scalar part
+        const int sg = sq_seg, first = sq_kt;
+        const int space = KSA_SEG(seg_space, sg);
+        {   // advance, unless this is the last tile
+            const int nk = first + BN;
+            const int run_done = nk >= KSA_SEG(seg_end, sg) ? 1 : 0;
+            const int more = (run_done ^ 1) | ((sg == 0 ? 1 : 0) & second_run);   // bitwise: no short-circuit branches
+            const int ns = sg + run_done, nkt = run_done ? seg_begin[1] : nk;
+            sq_seg = more ? ns : sq_seg, sq_kt = more ? nkt : sq_kt;
         }
+        const int per = space == KSA_SPACE_TEXT ? a.m : a.c;   // rows of the other kind per chunk
+        const int add = space == KSA_SPACE_TEXT ? 0 : a.c;
+        const int64_t arow = (int64_t)first + (int64_t)chunk_of(space, first) * per + add;
+        rq.k_base = kbase + arow * a.ks[1], rq.v_base = vbase + arow * a.ks[1];
+        rq.seg = sg, rq.first = first;
+        rq.full = first >= KSA_SEG(seg_full_lo, sg) && first + BN <= KSA_SEG(seg_full_hi, sg);
     };
-    auto request = [&](int sg, int key0, int buf) {
-        const int space = KSA_SEG(seg_space, sg), last = KSA_SEG(seg_end, sg) - 1;
-        load_tile_pair<D>(a, kbase, a.ks[1], vbase, a.ks[1], space, key0, last, lds + buf * 2 * BYTES,
-                          lds + buf * 2 * BYTES + BYTES, wave, lane);
+    auto prepare_row = [&](int i) {   // per-lane part of load instruction i
+        const int sg = rq.seg, first = rq.first;
+        const int space = KSA_SEG(seg_space, sg);
+        const int row = RW * wave + RPI * i + lane / CH;
+        int idx = first + row;
+        const int last = KSA_SEG(seg_end, sg) - 1;
+        idx = idx < last ? idx : last;
+        const int per = space == KSA_SPACE_TEXT ? a.m : a.c;
+        // augmented row of idx minus that of `first`: the index distance plus the other kind's rows in between
+        const int d_rows = (idx - first) + (chunk_of(space, idx) - chunk_of(space, first)) * per;
+        rq.off[i] = (unsigned)d_rows * kv_row_bytes + (unsigned)(((lane % CH) ^ swz<D>(row)) << 4);
     };
-    skip_empty_runs();
-    int buf = 0;
+    auto prepare_all = [&]() {
+        prepare_tile();
+#pragma unroll
+        for (int i = 0; i < NI; ++i) prepare_row(i);
+    };
+    const unsigned lds_tiles = (unsigned)(size_t)lds;
+    auto issue_load = [&](int buffer, int x) {   // load instruction x of the prepared tile: K rows, V rows alternating
+        const int i = x / 2;
+        const unsigned dst = lds_tiles + (unsigned)buffer * 2 * BYTES + (x % 2) * BYTES + (RW * wave + RPI * i) * (D * 2);
+        lds_direct_load_16_s(x % 2 == 0 ? rq.k_base : rq.v_base, rq.off[i], __builtin_amdgcn_readfirstlane(dst));
+    };
+
     // the wave's own rows and statistics have arrived before the first tile request: from here on only tile requests
     // are outstanding, and the waits in the loop count those alone
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    if (seg < n_seg) request(seg, kt, 0);
+    int fly_seg = 0, fly_kt = 0;   // the tile whose loads went out last: the next one to work on
+    bool fly_full = false;
+    if (n_tiles > 0) {   // (the host schedule has no item without tiles; nothing is requested for one)
+        prepare_all();
+        fly_seg = rq.seg, fly_kt = rq.first, fly_full = rq.full;
+#pragma unroll
+        for (int x = 0; x < 2 * NI; ++x) issue_load(0, x);
+        prepare_all();
+    }
+    int buf = 0;
     int elo[QB], espan[QB], range_seg = -1;
-    // One tile: publish it, request the next one, compute.  MASKED tiles clip every score to its row's visible range;
-    // tiles the schedule marks as seen whole by every row of the query tile do not.  The two variants are separate
-    // instantiations walked in stretches (as in the forward kernel), so that the loop body carries no branch.
+
+    // One tile: publish it, request the next one, compute.  The tile's work is a stream of MFMAs -- scores of key
+    // block 0 (S and dO V^T of both query blocks of the wave, k step by k step: every operand read from LDS feeds
+    // QB MFMAs), scores of key block 1, dQ products of block 0, of block 1 -- and one wave per SIMD has nobody else
+    // to fill the matrix pipe while its other instructions issue, so everything else is dealt into that stream by
+    // hand, one small piece behind each MFMA: the loads of the next request behind the first scores, the weights
+    // of block 0 behind the scores of block 1, the weights of block 1 behind the dQ products (of block 0, and of
+    // the first half of block 1, which only needs the first half of the weights), the arithmetic of the request after
+    // next behind the last dQ products.  Source order is the intended issue order, pinned with scheduling fences; LDS
+    // operands are read AHEAD operand steps before the MFMAs that consume them.  MASKED tiles clip every score to
+    // its row's visible range; tiles the schedule marks as seen whole by every row of the query tile do not: the two
+    // variants are separate instantiations walked in stretches.
     auto step = [&](auto masked_tag) {
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();   // tile (seg, kt) is complete in buffer buf; everybody is done with the other buffer
-        const int cur_seg = seg, cur_kt = kt;
-        kt += BN;
-        skip_empty_runs();
-        if (seg < n_seg) request(seg, kt, buf ^ 1);
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();   // the tile in work is complete in buffer buf; everybody is done with the other buffer
+        const int cur_seg = fly_seg, cur_kt = fly_kt;
+        fly_seg = rq.seg, fly_kt = rq.first, fly_full = rq.full;   // the tile whose loads go out during this step
         const int k_rows = buf * 2 * BYTES + ll.rows, v_rows = k_rows + BYTES, k_cols = buf * 2 * BYTES + ll.cols;
-        buf ^= 1;
+        const int req_buf = buf ^ 1;
+        constexpr int NU = 2 * KS + 4 * DB;   // operand steps: K and V rows per k step, then K columns per dQ product
+        constexpr int AHEAD = 3;
+        bf16x8 op_k[NU], op_v[2 * KS];
+        auto read_ops = [&](int u) {
+            if (u < 2 * KS) {
+                op_k[u] = read_rows<D>(lds, k_rows, u / KS, u % KS), op_v[u] = read_rows<D>(lds, v_rows, u / KS, u % KS);
+            } else {
+                const int kb = (u - 2 * KS) / (2 * DB), j = (u - 2 * KS) % (2 * DB);
+                op_k[u] = read_cols<D>(lds, k_cols, kb * 32 + (j / DB) * 16, j % DB);
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < AHEAD; ++u) read_ops(u);
         if (range_seg != cur_seg) {
             range_seg = cur_seg;
             const int space = KSA_SEG(seg_space, cur_seg), run_begin = KSA_SEG(seg_begin, cur_seg), run_end = KSA_SEG(seg_end, cur_seg);
@@ -329,114 +418,140 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
                 if (!q_valid[qb]) elo[qb] = 0x7fffffff, espan[qb] = 0;
             }
         }
-            // The tile's two 32-key blocks are two streams, each scores -> weights -> dQ, both query blocks of the wave
-            // together (every operand read from LDS feeds QB MFMAs).  One wave per SIMD has nobody else to fill the
-            // matrix pipe while its VALU block runs, so the streams are interleaved by hand: the weights of block 0 are
-            // computed in eight chunks with the score MFMAs of block 1 dealt between them, the weights of block 1 with
-            // the dQ MFMAs of block 0.  Source order is the intended issue order, pinned with scheduling fences; LDS
-            // operands are read one step ahead of the MFMAs that consume them.
-            constexpr int NC = 8;   // chunks of the VALU block: two scores per query block each
-            f32x16 sacc[2][QB], gacc[2][QB];
-            bf16x8 pb[2][QB][2];    // dS^T in the B-operand layout: lane = query, eight registers = eight keys
-            auto weights_chunk = [&](auto masked_tag, int kb, int c) {
-                constexpr bool MASKED = decltype(masked_tag)::value;
+        if constexpr (!POW2) {
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    // one subtraction and one unsigned compare per score: elo <= key < elo + espan
-                    const int rel = cur_kt + kb * 32 + 4 * h - elo[qb];
-#pragma unroll
-                    for (int g = 2 * c; g < 2 * c + 2; ++g) {
-                        float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][g], sl, -lse2[qb]));
-                        if constexpr (MASKED) p = (unsigned)(rel + 8 * (g / 4) + (g % 4)) < (unsigned)espan[qb] ? p : 0.f;
-                        pb[kb][qb][g / 8][g % 8] = (__bf16)(p * (gacc[kb][qb][g] - dl[qb]));
-                    }
-                }
-            };
-            auto weights = [&](int kb, int c) { weights_chunk(masked_tag, kb, c); };
-            auto score_step = [&](int kb, int s, const bf16x8 &k_op, const bf16x8 &v_op) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    if (s == 0) {
-                        mfma_score<true>(sacc[kb][qb], k_op, qreg[qb][0]);
-                        mfma_score<true>(gacc[kb][qb], v_op, greg[qb][0]);
-                    } else {
-                        mfma_score<false>(sacc[kb][qb], k_op, qreg[qb][s]);
-                        mfma_score<false>(gacc[kb][qb], v_op, greg[qb][s]);
-                    }
-                }
-            };
-            // dQ^T += K^T dS^T for the pair j = (16-key group hf, 32-column block db) of key block kb
-            auto dq_step = [&](int kb, int j, const bf16x8 &kt_op) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) mfma_acc(dqacc[qb][j % DB], kt_op, pb[kb][qb][j / DB]);
-            };
+            for (int x = 0; x < 2 * NI; ++x) issue_load(req_buf, x);
+            prepare_all();
+        }
+        KSA_FENCE();
 
-            // ---- scores of block 0 (alone on the matrix pipe)
-            {
-                bf16x8 ka[KS], va[KS];
+        f32x16 sacc[2][QB], gacc[2][QB];
+        bf16x8 pb[2][QB][2];    // dS^T in the B-operand layout: lane = query, eight registers = eight keys
+        float df[2][QB][16];
+        // weight of score register g (one key of the lane's query) of key block kb, query block qb; the bf16 pair
+        // is packed when its second member is done
+        auto weight = [&](int kb, int qb, int g) {
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][g], sl, -lse2[qb]));
+            // one subtraction and one unsigned compare per score: elo <= key < elo + espan
+            if constexpr (MASKED) p = (unsigned)(cur_kt + kb * 32 + 4 * h - elo[qb] + 8 * (g / 4) + (g % 4)) < (unsigned)espan[qb] ? p : 0.f;
+            df[kb][qb][g] = p * (gacc[kb][qb][g] - dl[qb]);
+            if (g % 2 == 1)
+                pb[kb][qb][g / 8][g % 8 - 1] = (__bf16)df[kb][qb][g - 1], pb[kb][qb][g / 8][g % 8] = (__bf16)df[kb][qb][g];
+        };
+        // element number e (0 .. 8 QB - 1) of a half (registers 8 hf .. 8 hf + 7) of block kb's weights: pairs of
+        // registers, the query blocks alternating
+        auto weight_of_half = [&](int kb, int hf, int e) {
+            const int pair = e / (2 * QB), qb = (e / 2) % QB;
+            weight(kb, qb, 8 * hf + 2 * pair + e % 2);
+        };
+
+        // scores of key block kb: slot = MFMA number within the phase
+        auto score_phase = [&](auto kb_tag) {
+            constexpr int kb = decltype(kb_tag)::value;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) ka[s] = read_rows<D>(lds, k_rows, 0, s), va[s] = read_rows<D>(lds, v_rows, 0, s);
-                KSA_FENCE();
+            for (int s = 0; s < KS; ++s) {
+                const int u = kb * KS + s;
+                if (u + AHEAD < NU) read_ops(u + AHEAD);
 #pragma unroll
-                for (int s = 0; s < KS; ++s) score_step(0, s, ka[s], va[s]);
-                KSA_FENCE();
-            }
-            // ---- weights of block 0 between the scores of block 1
-            {
-                bf16x8 ka[KS], va[KS];
-                ka[0] = read_rows<D>(lds, k_rows, 1, 0), va[0] = read_rows<D>(lds, v_rows, 1, 0);
-                scores_settle();
-                KSA_FENCE();
-#pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    if ((c * KS) % NC == 0) {
-                        const int s = c * KS / NC;
-                        if (s + 1 < KS) ka[s + 1] = read_rows<D>(lds, k_rows, 1, s + 1), va[s + 1] = read_rows<D>(lds, v_rows, 1, s + 1);
-                        score_step(1, s, ka[s], va[s]);
+                for (int y = 0; y < 2 * QB; ++y) {
+                    const int slot = s * 2 * QB + y, qb = y / 2;
+                    f32x16 &acc = y % 2 == 0 ? sacc[kb][qb] : gacc[kb][qb];
+                    const bf16x8 &a_op = y % 2 == 0 ? op_k[u] : op_v[u];
+                    const bf16x8 &b_op = y % 2 == 0 ? qreg[qb][s] : greg[qb][s];
+                    if (s == 0)
+                        mfma_score<true>(acc, a_op, b_op);
+                    else
+                        mfma_score<false>(acc, a_op, b_op);
+                    if constexpr (POW2 && kb == 0) {
+                        if (slot < 2 * NI) issue_load(req_buf, slot);
                     }
-                    weights(0, c);
+                    if constexpr (kb == 1) {
+                        // The scores of block 0 were completed by the MFMAs before this phase.  The compiler does not
+                        // know that the statements above are MFMAs: the empty statement keeps the code that reads
+                        // those scores behind the first two MFMAs of this phase, which take longer to issue than the
+                        // last results need to land.
+                        constexpr int PER = 16 * QB / (KS * 2 * QB) > 0 ? 16 * QB / (KS * 2 * QB) : 1;   // weights per slot
+                        if (slot == 1) {
+#pragma unroll
+                            for (int qq = 0; qq < QB; ++qq) asm volatile("" : "+v"(sacc[0][qq]), "+v"(gacc[0][qq]));
+#pragma unroll
+                            for (int z = 0; z < PER; ++z) {
+                                const int e = z;
+                                weight_of_half(0, e / (8 * QB), e % (8 * QB));
+                            }
+                        }
+                        if (slot >= 1) {
+#pragma unroll
+                            for (int z = 0; z < PER; ++z) {
+                                const int e = slot * PER + z;
+                                if (e < 16 * QB) weight_of_half(0, e / (8 * QB), e % (8 * QB));
+                            }
+                        }
+                    }
                     KSA_FENCE();
                 }
             }
-            // ---- weights of block 1 between the dQ products of block 0
-            bf16x8 kt1[2 * DB];
-            {
-                bf16x8 kt0[2 * DB];
-                kt0[0] = read_cols<D>(lds, k_cols, 0, 0);
-                scores_settle();
-                KSA_FENCE();
+        };
+        // dQ^T += K^T dS^T of key block kb: operand step j = (16-key group j / DB, 32-column block j % DB)
+        auto dq_phase = [&](auto kb_tag) {
+            constexpr int kb = decltype(kb_tag)::value;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    if ((c * 2 * DB) % NC == 0) {
-                        const int j = c * 2 * DB / NC;
-                        if (j + 1 < 2 * DB) kt0[j + 1] = read_cols<D>(lds, k_cols, ((j + 1) / DB) * 16, (j + 1) % DB);
-                        dq_step(0, j, kt0[j]);
-                    }
-                    weights(1, c);
-                    if (c == NC - 1) {
+            for (int j = 0; j < 2 * DB; ++j) {
+                const int u = 2 * KS + kb * 2 * DB + j;
+                if (u + AHEAD < NU) read_ops(u + AHEAD);
 #pragma unroll
-                        for (int j = 0; j < 2 * DB; ++j) kt1[j] = read_cols<D>(lds, k_cols, 32 + (j / DB) * 16, j % DB);
+                for (int qb = 0; qb < QB; ++qb) {
+                    const int slot = j * QB + qb;
+                    mfma_acc(dqacc[qb][j % DB], op_k[u], pb[kb][qb][j / DB]);
+                    if constexpr (kb == 0) {
+                        // first half of block 1's weights, one per MFMA (see above for the empty statement)
+                        if (slot == 1) {
+#pragma unroll
+                            for (int qq = 0; qq < QB; ++qq) asm volatile("" : "+v"(sacc[1][qq]), "+v"(gacc[1][qq]));
+                            weight_of_half(1, 0, 0);
+                        }
+                        if (slot >= 1 && slot < 8 * QB) weight_of_half(1, 0, slot);
+                        if (slot == 2 * DB * QB - 1) {   // fewer MFMAs than weights: the rest behind the last one
+#pragma unroll
+                            for (int e = 2 * DB * QB; e < 8 * QB; ++e) weight_of_half(1, 0, e);
+                        }
+                    } else {
+                        // second half of block 1's weights behind the products of the first half, two per MFMA; then
+                        // the arithmetic of the request after next
+                        constexpr int HALF = DB * QB;   // MFMAs of the first 16-key group
+                        if (slot < HALF) {
+#pragma unroll
+                            for (int e = slot * (8 * QB / HALF); e < (slot + 1) * (8 * QB / HALF); ++e) weight_of_half(1, 1, e);
+                        }
+                        if constexpr (POW2) {
+                            if (slot == HALF) prepare_tile();
+                            if (slot > HALF && slot - HALF - 1 < NI) prepare_row(slot - HALF - 1);
+                        }
                     }
                     KSA_FENCE();
                 }
             }
-            // ---- dQ products of block 1 (alone on the matrix pipe)
-#pragma unroll
-            for (int j = 0; j < 2 * DB; ++j) dq_step(1, j, kt1[j]);
-            KSA_FENCE();
+        };
+        score_phase(std::integral_constant<int, 0>{});
+        score_phase(std::integral_constant<int, 1>{});
+        dq_phase(std::integral_constant<int, 0>{});
+        dq_phase(std::integral_constant<int, 1>{});
+        buf ^= 1;
     };
-    auto tile_is_full = [&]() { return kt >= KSA_SEG(seg_full_lo, seg) && kt + BN <= KSA_SEG(seg_full_hi, seg); };
-    while (seg < n_seg) {
-        if (tile_is_full()) {
-            do step(std::false_type{});
-            while (seg < n_seg && tile_is_full());
+    int left = n_tiles;
+    while (left > 0) {
+        if (fly_full) {
+            do step(std::false_type{}), --left;
+            while (left > 0 && fly_full);
         } else {
-            do step(std::true_type{});
-            while (seg < n_seg && !tile_is_full());
+            do step(std::true_type{}), --left;
+            while (left > 0 && !fly_full);
         }
     }
 #undef KSA_SEG
 
+    // nothing of this workgroup is in flight any more when it leaves (the last request fetched a tile nobody reads)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     accumulators_settle();
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -676,14 +791,16 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // sits in front of their first use inside the loop, where it also waits for every tile in flight.)
     __builtin_amdgcn_s_waitcnt(0x0F70);
     // tiles 0 .. STAGES - 2 are requested up front; the request of tile STAGES - 1 is prepared for step 0
+    if (n_tiles > 0) {   // (a valid key is seen by its own row at least; nothing is requested otherwise)
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) {
+        for (int st = 0; st < STAGES - 1; ++st) {
+            prepare_all();
+            issue_flags(st);
+#pragma unroll
+            for (int x = 0; x < LOADS_PER_TILE; ++x) issue_load(st, x);
+        }
         prepare_all();
-        issue_flags(st);
-#pragma unroll
-        for (int x = 0; x < LOADS_PER_TILE; ++x) issue_load(st, x);
     }
-    prepare_all();
     int buf = 0;   // stage of the tile in work
 
     // One tile: publish it, request the tile STAGES - 1 ahead, compute.  The tile's work is a stream of 4 KS pairs of
@@ -939,14 +1056,20 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
     const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv((unsigned)((a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch));
     if (L.p.head_dim == 128) {
         hipLaunchKernelGGL(ksa_bwd_delta_kernel<128>, dim3((unsigned)delta_blocks), dim3(256), 0, st, a, n_rows);
-        hipLaunchKernelGGL(ksa_bwd_dq_kernel<128>, grid_dq, block, 0, st, a);
+        if (pow2)
+            hipLaunchKernelGGL((ksa_bwd_dq_kernel<128, true>), grid_dq, block, 0, st, a);
+        else
+            hipLaunchKernelGGL((ksa_bwd_dq_kernel<128, false>), grid_dq, block, 0, st, a);
         if (pow2)
             hipLaunchKernelGGL((ksa_bwd_dkv_kernel<128, true>), grid_dkv, block, 0, st, a);
         else
             hipLaunchKernelGGL((ksa_bwd_dkv_kernel<128, false>), grid_dkv, block, 0, st, a);
     } else {
         hipLaunchKernelGGL(ksa_bwd_delta_kernel<64>, dim3((unsigned)delta_blocks), dim3(256), 0, st, a, n_rows);
-        hipLaunchKernelGGL(ksa_bwd_dq_kernel<64>, grid_dq, block, 0, st, a);
+        if (pow2)
+            hipLaunchKernelGGL((ksa_bwd_dq_kernel<64, true>), grid_dq, block, 0, st, a);
+        else
+            hipLaunchKernelGGL((ksa_bwd_dq_kernel<64, false>), grid_dq, block, 0, st, a);
         if (pow2)
             hipLaunchKernelGGL((ksa_bwd_dkv_kernel<64, true>), grid_dkv, block, 0, st, a);
         else
