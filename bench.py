@@ -132,8 +132,8 @@ def main():
                     help="also run one 1 GiB device-to-device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--power-probe", type=float, default=0.0, metavar="SECONDS",
-                    help="loop the 128K prefill for this long while sampling the board's power and clocks with rocm-smi, "
-                         "print the samples as one JSON line and exit")
+                    help="loop the 128K prefill, an MFMA-only kernel and the 128K backward for this long each while "
+                         "sampling the board's power and clocks with amd-smi; print the samples as one JSON line and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -205,6 +205,12 @@ def main():
                                             args.power_probe)
         res["mfma_only_loop"]["tflops_last_call"] = round(tf.value, 1)
         res["mfma_only_loop"]["core_mhz_last_call"] = round(mhz.value, 0)
+        prefill()
+        g = synth.make_upstream_gradient(cfg, device="cuda")
+        gq, gk, gv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        bws = torch.empty(K.prefill_bwd_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+        res["prefill_backward_128k"] = power_probe(
+            lambda: K.ksa_prefill_bwd(lay, q, k, v, o, lse, g, dq=gq, dk=gk, dv=gv, workspace=bws), args.power_probe)
         print(json.dumps(res), flush=True)
         return
 
