@@ -419,14 +419,14 @@ def full_attention_reference(cfg, q, k, v, ksa_ms):
             "backward_frac_mfma_peak": round(2.5 * flops / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
-def mask_reference(cfg, label, c, m, C, note, with_backward=True):
-    """Not part of the timed step: another mask of the paper at the benchmark's length and heads through the same
-    library (seeded N(0,1) inputs of that shape)."""
+def mask_reference(cfg, label, c, m, C, note, with_backward=True, heads=None):
+    """Not part of the timed step: another mask of the paper at the benchmark's length and heads (or `heads` =
+    (query heads, KV heads)) through the same library (seeded N(0,1) inputs of that shape)."""
     import torch
     import paper_2604_24432_amd as K
     from paper_2604_24432_amd import synth
-    pc = synth.KsaConfig(label, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_text, c, m, C,
-                         seed=cfg.seed + 50 + c + C)
+    hq, hkv = heads if heads else (cfg.n_q_heads, cfg.n_kv_heads)
+    pc = synth.KsaConfig(label, cfg.batch, hq, hkv, cfg.head_dim, cfg.n_text, c, m, C, seed=cfg.seed + 50 + c + C)
     p = K.make_params(pc.batch, pc.n_text, pc.chunk_len, pc.n_summary, pc.window_chunks, pc.n_q_heads, pc.n_kv_heads,
                       pc.head_dim)
     lay = K.ksa_build_layout(p)
@@ -452,7 +452,11 @@ def mask_reference(cfg, label, c, m, C, note, with_backward=True):
 def paper_shape_reference(cfg):
     """The paper's own chunk form (one summary per chunk of 8 text tokens, 128 chunks of sliding window: table of model
     hyper-parameters)."""
-    return mask_reference(cfg, "paper_shape_128k", 8, 1, 128, "KSA in the paper's own form")
+    out = mask_reference(cfg, "paper_shape_128k", 8, 1, 128, "KSA in the paper's own form")
+    # the same mask with the head layout of the paper's other model (16 query heads, 16 KV heads: no grouping)
+    mha = mask_reference(cfg, "paper_shape_128k_h16", 8, 1, 128, "the same with 16 / 16 heads", with_backward=False, heads=(16, 16))
+    out["heads16_16"] = {k: mha[k] for k in ("workload", "ms", "live_tflops", "frac_mfma_peak")}
+    return out
 
 
 def sca_reference(cfg):
