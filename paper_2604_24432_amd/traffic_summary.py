@@ -1,11 +1,11 @@
 """Writes profiles/hbm_traffic.txt from the raw output of two rocprofv3 counter runs of bench.py.
 
     cd /tmp && export TMPDIR=/tmp && cd <repo>
-    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_fetch -o f -- \\
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d prof_out/fetch -o f -- \\
         python3 bench.py --steps 1 --warmup 0 --hot-path-only --traffic-probe
-    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_write -o w -- \\
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d prof_out/write -o w -- \\
         python3 bench.py --steps 1 --warmup 0 --hot-path-only --traffic-probe
-    python3 -m paper_2604_24432_amd.traffic_summary gpurun_out/prof_fetch gpurun_out/prof_write <commit>
+    python3 -m paper_2604_24432_amd.traffic_summary prof_out/fetch prof_out/write <commit>
 
 Both counters are reported in KiB per dispatch; each is scaled by what it reads for the 1 GiB device-to-device copy
 that --traffic-probe runs in the same process (FETCH_SIZE has been seen to report half of the bytes read).  The summary
