@@ -686,6 +686,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     if (ent.item < 0) return;
     const KsaWorkItem &item = a.items[ent.item];
     if ((item.pipelined != 0) != PIPELINED) return;
+    // The runs' few words are copied into scalar registers here: read through the reference at the start of each run
+    // they would be fetched from memory again (the tile requests are opaque memory operations to the compiler), one
+    // more memory round trip in front of every run's first tile request.
+    static_assert(KSA_MAX_SEGMENTS == 2, "run fields are selected with one compare");
+    int run_space[KSA_MAX_SEGMENTS], run_begin[KSA_MAX_SEGMENTS], run_end[KSA_MAX_SEGMENTS];
+    int run_full_lo[KSA_MAX_SEGMENTS], run_full_hi[KSA_MAX_SEGMENTS];
+#pragma unroll
+    for (int x = 0; x < KSA_MAX_SEGMENTS; ++x) {
+        run_space[x] = item.seg[x].space, run_begin[x] = item.seg[x].begin, run_end[x] = item.seg[x].end;
+        run_full_lo[x] = item.seg[x].full_lo, run_full_hi[x] = item.seg[x].full_hi;
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // this wave's query head and its block of 32*QB rows of the query tile
@@ -775,9 +786,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     const float raise_margin = RESCALE_THRESHOLD_LOG2 / sl;   // the rescale threshold in raw score units
 
     for (int seg = 0; seg < n_seg; ++seg) {
-        const int space = item.seg[seg].space, seg_begin = item.seg[seg].begin, seg_end = item.seg[seg].end;
+        const int space = seg == 0 ? run_space[0] : run_space[1];
+        const int seg_begin = seg == 0 ? run_begin[0] : run_begin[1], seg_end = seg == 0 ? run_end[0] : run_end[1];
         // tiles inside [full_lo, full_hi) are seen whole by every row of the query tile; the others are masked
-        const int full_lo = item.seg[seg].full_lo, full_hi = item.seg[seg].full_hi;
+        const int full_lo = seg == 0 ? run_full_lo[0] : run_full_lo[1], full_hi = seg == 0 ? run_full_hi[0] : run_full_hi[1];
         auto tile_masked = [&](int key0) { return !(key0 >= full_lo && key0 + BN <= full_hi); };
         const int n_tiles = (seg_end - seg_begin + BN - 1) / BN;
         // Are the lanes' row offsets the same for every tile of the run?  Yes when every tile starts at the same
