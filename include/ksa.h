@@ -129,7 +129,8 @@ int ksa_layout_launch_order(const ksa_layout *layout, int64_t *n_entries, uint8_
 
 /*
  * Bytes of device scratch memory ksa_prefill_fwd needs for this layout (0 for a NULL layout): room for a
- * key-major copy of V, batch * n_kv_heads * head_dim * (n_text + n_summary_tokens, each rounded up to 64) bf16.
+ * key-major copy of V, batch * n_kv_heads * head_dim * (n_text + n_summary_tokens, each rounded up to 64) bf16,
+ * followed by the largest squared K row norm per (batch, KV head, 64-key tile) and per (batch, KV head), fp32.
  */
 size_t ksa_prefill_workspace_bytes(const ksa_layout *layout);
 
@@ -140,8 +141,11 @@ size_t ksa_prefill_workspace_bytes(const ksa_layout *layout);
  *   *_strides = {batch, row, head} strides in elements; NULL = contiguous in the order above.
  *   lse: device fp32 [B, Hq, L] contiguous, natural-log sum-exp of the scaled visible scores; may be NULL.
  *   workspace: device memory, 16-byte aligned, at least ksa_prefill_workspace_bytes(layout) bytes, owned by the
- *   caller; the call overwrites it (a first kernel re-lays V out key-major for the main kernel) and needs it
- *   until the work enqueued on `stream` has finished.  Calls that share a workspace must be stream-ordered.
+ *   caller; the call overwrites it (a preparation pass re-lays V out key-major for the main kernel and takes the
+ *   largest K row norm of every KV head, from which the main kernel derives a fixed softmax reference per row
+ *   wherever |q| max |k| * scale is small enough to rule out overflow and underflow; other rows keep a running
+ *   maximum) and needs it until the work enqueued on `stream` has finished.  Calls that share a workspace must be
+ *   stream-ordered.
  *   stream: hipStream_t (NULL = default stream).
  * The main kernel walks the layout's schedule: bf16 MFMA for Q K^T and P V, fp32 online softmax.
  * Errors: INVALID_ARG (null tensors or workspace, misaligned pointers: 16-byte alignment required),
@@ -152,9 +156,10 @@ int ksa_prefill_fwd(ksa_layout *layout, const void *q, const void *k, const void
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * ksa_prefill_relayout_v: only the first kernel of ksa_prefill_fwd, the one that writes the key-major copy of
- * V into the workspace (same v, kv_strides, workspace and error rules as there).  ksa_prefill_fwd always runs it
- * itself; this entry point exists so that the two kernels can be timed apart.
+ * ksa_prefill_relayout_v: only the preparation pass of ksa_prefill_fwd, run on v alone: the key-major copy of V
+ * goes into the workspace (same v, kv_strides, workspace and error rules as there), and the row-norm part of the pass
+ * reads v in place of k (same shape, same cost; its result is not used by anything).  ksa_prefill_fwd always runs the
+ * pass itself; this entry point exists so that the pass and the main kernel can be timed apart.
  */
 int ksa_prefill_relayout_v(ksa_layout *layout, const void *v, const int64_t kv_strides[3], void *workspace,
                            size_t workspace_bytes, void *stream);

@@ -53,6 +53,8 @@ struct PrefillArgs {
     float *lse;
     int64_t qs[3], ks[3], os[3];   // {batch, row, head} strides in elements
     const __bf16 *vt;              // key-major copy of V per index space (see ksa_vt_kernel)
+    float *knorm_tiles;            // workspace: largest squared K row norm per (batch, KV head, 64-key tile)
+    float *knorm;                  // workspace: largest squared K row norm per (batch, KV head)
     int64_t vt_sum_off;            // element offset of the summary-space part of vt
     int32_t nt_pad, ns_pad;        // row lengths (keys) of the text / summary parts
     int32_t n_text, n_sum;         // keys per index space
@@ -485,7 +487,9 @@ __device__ __forceinline__ unsigned pack_pair(float w0, float w1) {
 // SYNC the per-tile barrier and the requests for the tile after next sit at the start of the P V slots.  Returns true
 // if some lane's next scores exceed its reference maximum by more than the threshold; mx_out holds the lane's maxima
 // (the lane pair of a row is only combined when a raise happens).
-template <int D, bool SYNC, bool MASKED, class Hook>
+// TRACK = false: the reference maximum is fixed for the whole work item (see static_reference() in the kernel): no row
+// maxima, no raise decision; a MASKED run still clips the next scores in the same slots.
+template <int D, bool SYNC, bool MASKED, bool TRACK, class Hook>
 __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, const bf16x8 (&qreg)[QB][Tile<D>::KS],
                                         f32x16 (&sv_next)[QB], const f32x16 (&sv_cur)[QB], bf16x8 (&ka)[Tile<D>::RING],
                                         int k_off, int v_off, int sb, int k_next_off, f32x16 (&oacc)[QB][Tile<D>::DB],
@@ -573,7 +577,7 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
                         sv_next[qb][x] = rel < (unsigned)vis_span[qb] ? sv_next[qb][x] : -INFINITY;
                     }
                 }
-                mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
+                if constexpr (TRACK) mx[qb] = max3(mx[qb], sv_next[qb][g], sv_next[qb][g + 1]);
             }
     };
     // ---- score slots ----
@@ -629,7 +633,7 @@ __device__ __forceinline__ bool subtile(unsigned char *lds, const LaneLds &ll, c
             for (int q2 = 0; q2 < QB; ++q2) scores_ready(sv_next[q2]);
         }
         valu_slice(N1 + u);
-        if (u == N2 - 2) {
+        if (TRACK && u == N2 - 2) {
             bool raise = false;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
@@ -761,12 +765,51 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     wlo_t = __builtin_amdgcn_readfirstlane(wlo_t), whi_t = __builtin_amdgcn_readfirstlane(whi_t);
     wlo_s = __builtin_amdgcn_readfirstlane(wlo_s), whi_s = __builtin_amdgcn_readfirstlane(whi_s);
 
+    // ---- the reference of the softmax -----------------------------------------------------------------
+    // Online softmax needs a reference m_i per row with s_ij - m_i bounded above.  The usual choice is the running
+    // row maximum (TRACK below: row maxima of every block, a raise of the reference with a rescale of the accumulators
+    // when a block exceeds it).  Where it is provably safe the pipelined kernel fixes the reference up front instead:
+    // |s_ij| = |q_i . k_j| <= |q_i| max_j |k_j| =: B_i (Cauchy-Schwarz; the largest K row norm of the KV head comes from
+    // the preparation pass), so with m_i = B_i - 64 / (scale log2 e) every exponent (s_ij - m_i) scale log2 e is at
+    // most 64, and at least 64 - 2 B_i scale log2 e.  If B_i scale log2 e <= 60 for every row of the wave, the exponents
+    // lie in [-56, 64]: no overflow, no underflow, whatever the data -- and no row maxima, no raise decision and no
+    // rescale in the loop (3 - 4 % of the time of the 128K workload).  The result is the same softmax: the reference
+    // cancels in O = sum(p v) / sum(p) and is added back in the log-sum-exp.  Waves whose bound is larger (keys or
+    // queries of unusual size) or not a number take the tracking variant; both variants execute the same barriers,
+    // so the waves of a workgroup may differ.
+    float m_static[QB];
+    bool static_ok = false;
+    if constexpr (PIPELINED) {
+        const float kmax2 = a.knorm[b * a.n_kv_heads + hkv];
+        bool ok = true;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float n2 = 0.f;
+#pragma unroll
+            for (int s = 0; s < T::KS; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) n2 = fmaf((float)qreg[qb][s][e], (float)qreg[qb][s][e], n2);
+            n2 += other_half(n2);                                        // the lane pair of a row holds its two halves
+            const float bound = __builtin_sqrtf(n2 * kmax2) * 1.002f;    // raw score units; the factor covers fp32 rounding
+            ok &= bound * a.scale_log2e <= 60.f;                         // false for NaN
+            m_static[qb] = bound - 64.f / a.scale_log2e;
+        }
+        static_ok = __builtin_amdgcn_ballot_w64(!ok) == 0;
+    } else {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) m_static[qb] = 0.f;
+    }
+
+    // Everything from the accumulators to the stores, once per variant (two copies of the code that share nothing but
+    // the prologue above: a choice inside the loops would join the variants with the accumulators live).
+    auto body = [&](auto track_tag) {
+    constexpr bool TRACK = decltype(track_tag)::value;
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 oacc[QB][T::DB];
     RowState st;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        st.m_ref[qb] = -1e30f;
+        st.m_ref[qb] = TRACK ? -1e30f : m_static[qb];
         st.l_part[qb] = 0.f;
         st.l_sum[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -871,12 +914,14 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                         }
                     }
                     float mx = -INFINITY;
+                    if constexpr (TRACK) {
 #pragma unroll
-                    for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
+                        for (int g = 0; g < 16; g += 2) mx = max3(mx, sv_a[qb][g], sv_a[qb][g + 1]);
+                        raise |= mx > st.m_ref[qb] + raise_margin;
+                    }
                     mxl[qb] = mx;
-                    raise |= mx > st.m_ref[qb] + raise_margin;
                 }
-                if (seg == 0) {
+                if (TRACK && seg == 0) {
                     // nothing has been accumulated yet, so the reference maximum simply starts at the first block's row
                     // maximum: no rescale of the (zero) accumulators and row sums.  A row that sees none of these keys
                     // keeps its start value and is raised by the first block it does see.
@@ -885,7 +930,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                         st.m_ref[qb] = fmaxf(st.m_ref[qb], fmaxf(mxl[qb], other_half(mxl[qb])));
                     raise = false;
                 }
-                raise = __builtin_amdgcn_ballot_w64(raise) != 0;
+                if constexpr (TRACK) raise = __builtin_amdgcn_ballot_w64(raise) != 0;
                 bf16x8 ka_pre[T::RING];
 #pragma unroll
                 for (int s = 0; s < T::RING; ++s) ka_pre[s] = read_k_operand<D>(lds, ll.k + K0 + HALF, s);
@@ -930,8 +975,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                                 prepare_request();
                                 raise = false;
                             } else {
-                                if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                                raise = subtile<D, false, MASKED>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur,
+                                if (TRACK && raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                                raise = subtile<D, false, MASKED, TRACK>(lds, ll, qreg, sv_a, sv_b, ka_pre, K0 + b_nxt, V0 + b_cur,
                                                                   1, K0 + b_nxt + HALF, oacc, st, ind, sl, raise_margin, mxl,
                                                                   sync, key0, vis_lo, vis_span, prepare_request) &&
                                         (tn < n_tiles);
@@ -948,8 +993,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                                 idle_subtile<D, true>(lds, ll, sv_b, ka_pre, K0 + b_nxt, mxl, sync);
                                 raise = false;
                             } else {
-                                if (raise) raise_reference_pl<D>(st, mxl, oacc, sl);
-                                raise = subtile<D, true, MASKED>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF,
+                                if (TRACK && raise) raise_reference_pl<D>(st, mxl, oacc, sl);
+                                raise = subtile<D, true, MASKED, TRACK>(lds, ll, qreg, sv_b, sv_a, ka_pre, K0 + b_cur + HALF,
                                                                  V0 + b_cur, 0, K0 + b_nxt, oacc, st, ind, sl, raise_margin,
                                                                  mxl, sync, key0 + 32, vis_lo, vis_span, [] {});
                             }
@@ -1052,6 +1097,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                 a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
         }
     }
+    };
+    if constexpr (PIPELINED) {
+        if (static_ok)
+            body(std::false_type{});
+        else
+            body(std::true_type{});
+    } else {
+        body(std::true_type{});
+    }
 }
 
 // Key-major copy of V for the pipelined loop.  The P V MFMA wants, per lane, eight keys of one head-dim column; V is
@@ -1093,14 +1147,79 @@ __global__ __launch_bounds__(256) void ksa_vt_kernel(const PrefillArgs a, int ti
         for (int e = 0; e < 8; ++e) x[e] = raw[first + 8 * (e / 4) + e % 4][d];
         *reinterpret_cast<u16x8 *>(out + (int64_t)d * stride + 8 * pc) = x;
     }
+    // The same pass takes the largest squared row norm of the tile's K rows (for the attention kernel's static softmax
+    // reference): one value per (batch, KV head, tile), reduced per (batch, KV head) by ksa_knorm_reduce_kernel.
+    {
+        __shared__ float wave_best[4];
+        const __bf16 *kb = a.k + b * a.ks[0] + hkv * a.ks[2];
+        float best = 0.f;
+        for (int idx = tid; idx < 64 * CH; idx += 256) {
+            const int row = idx / CH, ch = idx % CH;
+            float s2 = 0.f;
+            if (k0 + row < n_space) {
+                const bf16x8 x = *reinterpret_cast<const bf16x8 *>(kb + (int64_t)aug_row(a, space, k0 + row) * a.ks[1] + ch * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s2 = fmaf((float)x[e], (float)x[e], s2);
+            }
+#pragma unroll
+            for (int dd = CH / 2; dd > 0; dd >>= 1) s2 += __shfl_xor(s2, dd);   // the CH lanes of a row are neighbours
+            best = fmaxf(best, s2);
+        }
+#pragma unroll
+        for (int dd = 32; dd > 0; dd >>= 1) best = fmaxf(best, __shfl_xor(best, dd));
+        if ((tid & 63) == 0) wave_best[tid >> 6] = best;
+        __syncthreads();
+        if (tid == 0)
+            a.knorm_tiles[((int64_t)(b * a.n_kv_heads + hkv)) * gridDim.x + blockIdx.x] =
+                fmaxf(fmaxf(wave_best[0], wave_best[1]), fmaxf(wave_best[2], wave_best[3]));
+    }
+}
+
+// knorm[(batch, KV head)] = max over that head's tiles of knorm_tiles.  A NaN anywhere gives NaN (which sends the
+// attention kernel to its tracking variant).
+__global__ __launch_bounds__(256) void ksa_knorm_reduce_kernel(const float *tiles, float *out, int n_tiles) {
+    __shared__ float wave_best[4];
+    const float *src = tiles + (int64_t)blockIdx.x * n_tiles;
+    float best = 0.f;
+    bool bad = false;
+    for (int i = threadIdx.x; i < n_tiles; i += 256) {
+        const float x = src[i];
+        bad |= !(x == x);
+        best = fmaxf(best, x);
+    }
+    if (bad) best = __builtin_nanf("");
+#pragma unroll
+    for (int dd = 32; dd > 0; dd >>= 1) {
+        const float o = __shfl_xor(best, dd);
+        best = (best != best || o != o) ? __builtin_nanf("") : fmaxf(best, o);
+    }
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = wave_best[0];
+        for (int w = 1; w < 4; ++w) r = (r != r || wave_best[w] != wave_best[w]) ? __builtin_nanf("") : fmaxf(r, wave_best[w]);
+        out[blockIdx.x] = r;
+    }
 }
 
 }  // namespace
 
-size_t ksa_prefill_workspace_size(const ksa_params &p) {
+namespace {
+// workspace: [key-major copy of V][largest squared K row norm per (batch, KV head, 64-key tile)][... per (batch, KV head)]
+int64_t vt_bytes(const ksa_params &p) {
     const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
     const int64_t keys = (p.n_text + 63) / 64 * 64 + (n_sum + 63) / 64 * 64;
-    return (size_t)((int64_t)p.batch * p.n_kv_heads * p.head_dim * keys * 2);
+    return (int64_t)p.batch * p.n_kv_heads * p.head_dim * keys * 2;   // a multiple of 128 * head_dim bytes
+}
+int64_t key_tiles(const ksa_params &p) {
+    const int64_t n_sum = (int64_t)(p.n_text / p.chunk_len) * p.n_summary;
+    return (p.n_text + 63) / 64 + (n_sum + 63) / 64;
+}
+}  // namespace
+
+size_t ksa_prefill_workspace_size(const ksa_params &p) {
+    const int64_t heads = (int64_t)p.batch * p.n_kv_heads;
+    return (size_t)(vt_bytes(p) + (heads * key_tiles(p) + heads) * (int64_t)sizeof(float));
 }
 
 
@@ -1135,6 +1254,8 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
     a.nt_pad = (a.n_text + 63) / 64 * 64;
     a.ns_pad = (a.n_sum + 63) / 64 * 64;
     a.vt = static_cast<const __bf16 *>(L.workspace);
+    a.knorm_tiles = reinterpret_cast<float *>(static_cast<unsigned char *>(L.workspace) + vt_bytes(L.p));
+    a.knorm = a.knorm_tiles + (int64_t)L.p.batch * L.p.n_kv_heads * key_tiles(L.p);
     a.vt_sum_off = (int64_t)L.p.batch * L.p.n_kv_heads * L.p.head_dim * a.nt_pad;
     if (!L.workspace || L.workspace_bytes < ksa_prefill_workspace_size(L.p)) return KSA_ERR_WORKSPACE_TOO_SMALL;
     if (L.n_entries <= 0) return KSA_OK;
@@ -1156,6 +1277,8 @@ int ksa_launch_prefill(const KsaPrefillLaunch &L, void *stream) {
             hipLaunchKernelGGL(ksa_vt_kernel<64>, grid, dim3(256), 0, st, a, tiles_text);
         else
             return KSA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(ksa_knorm_reduce_kernel, dim3(L.p.batch * L.p.n_kv_heads), dim3(256), 0, st, a.knorm_tiles, a.knorm,
+                           tiles_text + tiles_sum);
         if (hipGetLastError() != hipSuccess) return KSA_ERR_HIP;
     }
     if (!(L.phases & 2)) return KSA_OK;

@@ -348,10 +348,26 @@ def test_relayout_v_is_the_documented_permutation(name):
     ws = torch.full((K.prefill_workspace_bytes(lay),), 0x5A, dtype=torch.uint8, device="cuda")
     K.ksa_prefill_relayout_v(lay, v.cuda(), ws)
     torch.cuda.synchronize()
-    got = ws.cpu().numpy().view(np.int16)
     want = expected_key_major_v(cfg, v)
+    got = ws.cpu().numpy()[:want.nbytes].view(np.int16)      # the copy comes first in the workspace
     assert got.shape == want.shape
     assert np.array_equal(got, want)
+
+
+def test_preparation_pass_takes_the_largest_key_norm():
+    """The workspace ends with the largest squared K row norm per (batch, KV head), which the attention kernel's static
+    softmax reference is derived from (|q . k| <= |q| max |k|): compared with the norms computed by torch."""
+    cfg = synth.KsaConfig("key_norms", 2, 4, 2, 128, 600, 64, 8, 1, seed=4242, key_outlier_frac=0.01)
+    q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
+    lay = K.ksa_build_layout(params_of(cfg))
+    ws = torch.full((K.prefill_workspace_bytes(lay),), 0x5A, dtype=torch.uint8, device="cuda")
+    K.ksa_prefill_fwd(lay, q, k, v, workspace=ws)
+    torch.cuda.synchronize()
+    heads = cfg.batch * cfg.n_kv_heads
+    got = ws.cpu().numpy()[-4 * heads:].view(np.float32).reshape(cfg.batch, cfg.n_kv_heads)
+    want = (k.float() ** 2).sum(dim=-1).amax(dim=1).cpu().numpy()          # [B, Hkv]
+    say(f"key norms: got {got.ravel()} want {want.ravel()}")
+    assert np.allclose(got, want, rtol=1e-5)
 
 
 def test_repeatable_32k_outlier_keys():

@@ -197,7 +197,9 @@ def test_bad_arguments_are_reported_without_a_gpu():
     # a workspace that is too small is reported as such (fake, never dereferenced, 16-byte aligned addresses)
     fake = ctypes.c_void_p(4096)
     need = K.prefill_workspace_bytes(lay)
-    assert need == 1 * 2 * 64 * (128 + 64) * 2          # batch * Hkv * d * (n_text + 16 summaries rounded up to 64) bf16
+    # batch * Hkv * d * (n_text + 16 summaries rounded up to 64) bf16, then one fp32 per (batch, KV head, 64-key tile:
+    # 2 text tiles + 1 summary tile) and one per (batch, KV head)
+    assert need == 1 * 2 * 64 * (128 + 64) * 2 + (1 * 2 * 3 + 1 * 2) * 4
     rc = binding.lib().ksa_prefill_fwd(lay.handle, fake, fake, fake, fake, None, None, None, None, fake, need - 1, None)
     assert rc == -3
     rc = binding.lib().ksa_decode_fwd(ctypes.byref(p), None, None, None, None, None, None, None, None, 0, 0, None)
