@@ -271,7 +271,7 @@ def main():
                    "layout_build_ms": round(layout_ms, 2), "build": K.build_info()},
         "prefill": {"ms": round(pre_avg, 4), "ms_min": round(float(np.min(pre_ms)), 4), "live_flops": live_flops,
                     "live_tflops": round(pre_tflops, 2), "frac_mfma_peak": round(pre_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "relayout_v_kernel_ms": round(vt_avg, 4), "attention_kernel_ms": round(attn_avg, 4),
+                    "preparation_pass_ms": round(vt_avg, 4), "attention_kernel_ms": round(attn_avg, 4),
                     "tile_issued_flops": issued_flops, "issued_over_live": round(issued_flops / live_flops, 4),
                     "heads_per_workgroup": lay.heads_per_workgroup, "q_tile_rows": lay.q_tile_rows},
         "decode": {"ms": round(dec_avg, 5), "ms_min": round(float(np.min(dec_ms)), 5), "bytes": dec_bytes,
