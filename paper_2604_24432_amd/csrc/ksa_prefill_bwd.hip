@@ -40,7 +40,7 @@ struct BwdArgs {
     // workspace: per-row statistics in COMPACT order, [B, Hq, nt_pad + ns_pad] fp32 each: position p < nt_pad is
     // text index p, position nt_pad + u is summary ordinal u; rows past the end of an index space hold zeros
     float *lse2c;                             // log-sum-exp times log2(e)
-    float *dlc;                               // delta_i = dO_i . O_i
+    float *dlc;                               // MINUS delta_i = -(dO_i . O_i): added to dP, or the start value of its MFMAs
     int32_t nt_pad, ns_pad;                   // rows per index space rounded up to 64
     __bf16 *dq, *dk, *dv;
     int64_t qs[3], ks[3], os[3], dqs[3], dks[3];   // {batch, row, head} strides in elements (os: o and g)
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void ksa_bwd_delta_kernel(const BwdArgs a, int
 #pragma unroll
     for (int d = CH / 2; d > 0; d >>= 1) s += __shfl_xor(s, d);
     if (in_grid && piece == 0) {
-        a.dlc[slot] = s;
+        a.dlc[slot] = -s;
         a.lse2c[slot] = l2;
     }
 }
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
             float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][g], sl, -lse2[qb]));
             // one subtraction and one unsigned compare per score: elo <= key < elo + espan
             if constexpr (MASKED) p = (unsigned)(cur_kt + kb * 32 + 4 * h - elo[qb] + 8 * (g / 4) + (g % 4)) < (unsigned)espan[qb] ? p : 0.f;
-            df[kb][qb][g] = p * (gacc[kb][qb][g] - dl[qb]);
+            df[kb][qb][g] = p * (gacc[kb][qb][g] + dl[qb]);   // dl holds minus delta
             if (g % 2 == 1)
                 pb[kb][qb][g / 8][g % 8 - 1] = (__bf16)df[kb][qb][g - 1], pb[kb][qb][g / 8][g % 8] = (__bf16)df[kb][qb][g];
         };
@@ -850,17 +850,27 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
         KSA_FENCE();
 
         // statistics of rows 8 gg + 4 h .. + 3 of block qb: the rows of a lane's score registers 4 gg .. 4 gg + 3
-        struct Stats { f32x4 l4, d4; int4 lo4, span4; };
+        struct Stats { f32x4 l4; int4 lo4, span4; };
         Stats stats[2][4];
         auto read_stats = [&](int qb, int gg) {
             const int row0 = qb * 32 + 8 * gg + 4 * h;
             stats[qb][gg].l4 = *reinterpret_cast<const f32x4 *>(&st_lse[buf][row0]);
-            stats[qb][gg].d4 = *reinterpret_cast<const f32x4 *>(&st_dl[buf][row0]);
             if constexpr (MASKED) {
                 stats[qb][gg].lo4 = *reinterpret_cast<const int4 *>(&st_lo[buf][row0]);
                 stats[qb][gg].span4 = *reinterpret_cast<const int4 *>(&st_span[buf][row0]);
             }
         };
+        // dP of block qb starts from minus delta of its rows (the workspace holds it with that sign), read straight into
+        // the accumulator of the dO V^T MFMAs: the subtraction dP - delta costs no instruction
+        auto start_dp = [&](int qb) {
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                const f32x4 nd = *reinterpret_cast<const f32x4 *>(&st_dl[buf][qb * 32 + 8 * gg + 4 * h]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) gacc[qb][4 * gg + e] = nd[e];
+            }
+        };
+        start_dp(0);
         // weights of score register g of block qb (one query row of the lane's key); the bf16 pair is packed when
         // its second member is done
         float pf[2][16], df[2][16];
@@ -873,7 +883,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
             // one subtraction and one unsigned compare: lo <= key < lo + span
             if constexpr (MASKED) p = (unsigned)(key - lo_e[e]) < (unsigned)span_e[e] ? p : 0.f;
             pf[qb][g] = p;
-            df[qb][g] = p * (gacc[qb][g] - cur.d4[e]);
+            df[qb][g] = p * gacc[qb][g];   // gacc = dO . v - delta: its MFMAs started from minus delta
             if (g % 2 == 1) {
                 pp[qb][g / 8][g % 8 - 1] = (__bf16)pf[qb][g - 1], pp[qb][g / 8][g % 8] = (__bf16)pf[qb][g];
                 pd[qb][g / 8][g % 8 - 1] = (__bf16)df[qb][g - 1], pd[qb][g / 8][g % 8] = (__bf16)df[qb][g];
@@ -899,13 +909,15 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
                 for (int half = 0; half < 2; ++half) {
                     const int slot = 2 * x + half;   // MFMA number within the phase
                     if constexpr (ph < 2) {
-                        f32x16 &acc = half == 0 ? sacc[ph] : gacc[ph];
-                        const bf16x8 &a_op = half == 0 ? op_q[i] : op_g[i];
-                        const bf16x8 &b_op = half == 0 ? kreg[x] : vreg[x];
-                        if (x == 0)
-                            mfma_score<true>(acc, a_op, b_op);
-                        else
-                            mfma_score<false>(acc, a_op, b_op);
+                        if (half == 0) {
+                            if (x == 0)
+                                mfma_score<true>(sacc[ph], op_q[i], kreg[x]);
+                            else
+                                mfma_score<false>(sacc[ph], op_q[i], kreg[x]);
+                        } else {
+                            mfma_score<false>(gacc[ph], op_g[i], vreg[x]);   // started from minus delta
+                        }
+                        if (ph == 0 && x == KS - 3 && half == 1) start_dp(1);
                     } else if (half == 0) {
                         // dV^T += G^T P, dK^T += Q^T dS for (16-row group x / DB, 32-column block x % DB) of block ph - 2
                         mfma_acc(dvacc[x % DB], op_g[i], pp[ph - 2][x / DB]);
