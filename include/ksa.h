@@ -180,10 +180,10 @@ size_t ksa_prefill_bwd_workspace_bytes(const ksa_layout *layout);
  *   and dv is written.
  *   workspace: device memory, 16-byte aligned, at least ksa_prefill_bwd_workspace_bytes(layout) bytes, owned by
  *   the caller, overwritten, needed until the work enqueued on `stream` has finished.
- * No atomics: results do not depend on the launch order.  head_dim 64 or 128.  The row strides of q and d_o must be
- * positive, and the rows that 64 consecutive text (or summary) positions span in the augmented sequence must lie
- * within 4 GiB of each other in q and in d_o (a chunk_len of 4096 at a row stride of 8 KiB still does); else
- * UNSUPPORTED.
+ * No atomics: results do not depend on the launch order.  head_dim 64 or 128.  The row strides of q, k / v and d_o
+ * must be positive, and the rows that 64 consecutive text (or summary) positions span in the augmented sequence must
+ * lie within 4 GiB of each other in each of these tensors (a chunk_len of 4096 at a row stride of 8 KiB still does);
+ * else UNSUPPORTED.
  * Errors: INVALID_ARG (null or misaligned pointers, bad strides), WORKSPACE_TOO_SMALL, UNSUPPORTED, HIP.
  */
 int ksa_prefill_bwd(ksa_layout *layout, const void *q, const void *k, const void *v, const void *o, const float *lse,

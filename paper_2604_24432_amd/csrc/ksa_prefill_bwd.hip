@@ -1058,12 +1058,15 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
         ((int64_t)a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch >= ((int64_t)1 << 31))
         return KSA_ERR_UNSUPPORTED;
     const bool pow2 = a.c_shift >= 0 && (a.m == 0 || a.m_shift >= 0);
-    {   // the dK/dV kernel addresses the rows of a query tile by unsigned 32-bit byte offsets from the tile's first row
+    {   // both kernels address the rows of a streamed tile (Q and dO in the dK/dV kernel, K and V in the dQ kernel) by
+        // unsigned 32-bit byte offsets from the tile's first row
         const int64_t span_text = 63 + (63 / a.c + 1) * (int64_t)a.m;
         const int64_t span_sum = a.m > 0 ? 63 + (63 / a.m + 1) * (int64_t)a.c : 0;
         const int64_t span = span_text > span_sum ? span_text : span_sum;
-        const int64_t row_elems = a.qs[1] > a.os[1] ? a.qs[1] : a.os[1];
-        if (a.qs[1] <= 0 || a.os[1] <= 0 || span * row_elems * 2 + 2 * L.p.head_dim >= ((int64_t)1 << 32)) return KSA_ERR_UNSUPPORTED;
+        int64_t row_elems = a.qs[1] > a.os[1] ? a.qs[1] : a.os[1];
+        row_elems = row_elems > a.ks[1] ? row_elems : a.ks[1];
+        if (a.qs[1] <= 0 || a.os[1] <= 0 || a.ks[1] <= 0 || span * row_elems * 2 + 2 * L.p.head_dim >= ((int64_t)1 << 32))
+            return KSA_ERR_UNSUPPORTED;
     }
     const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv((unsigned)((a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch));
     if (L.p.head_dim == 128) {

@@ -321,3 +321,29 @@ def test_prefill_4k_sampled_rows():
     k_rows = sorted(set([aug_text(cfg, int(x)) for x in rng.integers(0, cfg.n_text, 5)] +
                         [aug_summary(cfg, int(x)) for x in rng.integers(0, n_sum, 5)] + [aug_summary(cfg, 0)]))
     sampled_compare(cfg, q_rows, k_rows, cfg.name)
+
+
+def test_rows_too_far_apart_are_refused_before_any_launch():
+    """The kernels address the rows of a streamed tile by 32-bit byte offsets from the tile's first row: a row stride
+    that puts the rows of one tile more than 4 GiB apart is reported as unsupported by the argument checks of the
+    launch (nothing is enqueued, so the made-up stride is never used for an access)."""
+    import ctypes as C
+    from paper_2604_24432_amd import binding
+    cfg = synth.KsaConfig("far_rows", 1, 4, 2, 128, 256, 64, 8, 1, seed=5)
+    q, k, v = (x.cuda() for x in synth.make_prefill_inputs(cfg))
+    g = synth.make_upstream_gradient(cfg).cuda()
+    lay = K.ksa_build_layout(params_of(cfg))
+    o, lse = K.ksa_prefill_fwd(lay, q, k, v)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(K.prefill_bwd_workspace_bytes(lay), dtype=torch.uint8, device="cuda")
+    far = (C.c_int64 * 3)(0, 1 << 23, 128)            # 16 MiB between consecutive rows: 575 rows of a tile span 9 GiB
+    near = lambda t: (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+    for which in ("q", "kv", "o"):
+        rc = binding.lib().ksa_prefill_bwd(
+            lay.handle, C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
+            C.c_void_p(o.data_ptr()), C.c_void_p(lse.data_ptr()), C.c_void_p(g.data_ptr()), C.c_void_p(dq.data_ptr()),
+            C.c_void_p(dk.data_ptr()), C.c_void_p(dv.data_ptr()), far if which == "q" else near(q),
+            far if which == "kv" else near(k), far if which == "o" else near(o), near(dq), near(dk),
+            C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), None)
+        assert rc == -2, which                         # KSA_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
