@@ -697,6 +697,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     static_assert(LOADS_PER_TILE <= 2 * KS, "one load behind each MFMA of the first score block");
     const int stats_stride = a.nt_pad + a.ns_pad;
     const unsigned q_row_bytes = (unsigned)a.qs[1] * 2u, g_row_bytes = (unsigned)a.os[1] * 2u;
+    // bases of the KV head's first query head, and strides as unsigned 32-bit element counts
+    const __bf16 *q_wg = a.q + b * a.qs[0] + (int64_t)hkv * a.group * a.qs[2];
+    const __bf16 *g_wg = a.g + b * a.os[0] + (int64_t)hkv * a.group * a.os[2];
+    const float *lse_wg = a.lse2c + ((int64_t)b * a.n_q_heads + hkv * a.group) * stats_stride;
+    const float *dl_wg = a.dlc + ((int64_t)b * a.n_q_heads + hkv * a.group) * stats_stride;
+    const unsigned q_row_elems = (unsigned)a.qs[1], g_row_elems = (unsigned)a.os[1];
+    const unsigned q_head_elems = (unsigned)a.qs[2], g_head_elems = (unsigned)a.os[2];
     // the next tile of the sequence; stays on the last tile once the sequence is exhausted
     int sq_run = run_tiles[0] > 0 ? 0 : 1, sq_ti = 0, sq_hj = 0;
     struct Request {
@@ -715,9 +722,8 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
         return idx / (sp == KSA_SPACE_TEXT ? a.c : a.m);
     };
     auto prepare_tile = [&]() {   // scalar part
-        const int run = sq_run, cur_ti = sq_ti;
+        const int run = sq_run, cur_ti = sq_ti, cur_hj = sq_hj;
         const int first = (KSA_RUN(run_first_blk, run) + KSA_RUN(run_tiles, run) - 1 - sq_ti) * BN;
-        const int head = hkv * a.group + sq_hj;
         {   // advance, unless this is the last tile
             int hj = sq_hj + 1, ti = sq_ti, rn = sq_run;
             const bool wrap = hj == a.group;
@@ -729,11 +735,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
         }
         const int per = run == KSA_SPACE_TEXT ? a.m : a.c;   // rows of the other kind per chunk
         const int add = run == KSA_SPACE_TEXT ? 0 : a.c;
-        const int64_t arow = (int64_t)first + (int64_t)chunk_of(run, first) * per + add;
-        rq.q_base = a.q + b * a.qs[0] + head * a.qs[2] + arow * a.qs[1];
-        rq.g_base = a.g + b * a.os[0] + head * a.os[2] + arow * a.os[1];
-        const int64_t at = ((int64_t)b * a.n_q_heads + head) * stats_stride + (run == KSA_SPACE_TEXT ? 0 : a.nt_pad) + first;
-        rq.lse_p = a.lse2c + at, rq.dl_p = a.dlc + at;
+        // (unsigned 32 x 32 -> 64 bit products from per-workgroup bases: a handful of scalar instructions; the launch
+        // checks that the strides fit)
+        const unsigned arow = (unsigned)(first + chunk_of(run, first) * per + add);
+        rq.q_base = q_wg + ((uint64_t)arow * q_row_elems + (uint64_t)(unsigned)cur_hj * q_head_elems);
+        rq.g_base = g_wg + ((uint64_t)arow * g_row_elems + (uint64_t)(unsigned)cur_hj * g_head_elems);
+        const uint64_t at = (uint64_t)(unsigned)cur_hj * (unsigned)stats_stride + (unsigned)((run == KSA_SPACE_TEXT ? 0 : a.nt_pad) + first);
+        rq.lse_p = lse_wg + at, rq.dl_p = dl_wg + at;
         rq.q_space = run, rq.first = first;
         const int bi = KSA_RUN(run_tiles, run) - 1 - cur_ti;
         rq.full = bi >= KSA_RUN(full_lo_blk, run) && bi < KSA_RUN(full_hi_blk, run);
@@ -1067,6 +1075,8 @@ int ksa_launch_prefill_bwd(const KsaPrefillBwdLaunch &L, void *stream) {
         row_elems = row_elems > a.ks[1] ? row_elems : a.ks[1];
         if (a.qs[1] <= 0 || a.os[1] <= 0 || a.ks[1] <= 0 || span * row_elems * 2 + 2 * L.p.head_dim >= ((int64_t)1 << 32))
             return KSA_ERR_UNSUPPORTED;
+        // ... and the dK/dV kernel multiplies the head strides of q and d_o as unsigned 32-bit numbers
+        if (a.qs[2] >= ((int64_t)1 << 32) || a.os[2] >= ((int64_t)1 << 32) || L.aug_len >= ((int64_t)1 << 31)) return KSA_ERR_UNSUPPORTED;
     }
     const dim3 block(NW * 64), grid_dq(L.n_entries), grid_dkv((unsigned)((a.sum_tiles + text_tiles) * L.p.n_kv_heads * L.p.batch));
     if (L.p.head_dim == 128) {
