@@ -107,6 +107,26 @@ def test_effective_mask_of_the_kernel_is_bit_exact_on_tiny():
     assert np.array_equal(np.rint(counts).astype(np.int64), want_mask.sum(axis=1))
 
 
+def test_fixed_and_running_reference_side_by_side():
+    """The pipelined kernel fixes the softmax reference per row from |q| max |k| where that bound is small and keeps a
+    running maximum elsewhere, wave by wave.  Here one query head of every group is scaled by 4 (its bound, about 80
+    in the exponent domain, is above the limit of 60; the plain heads are at about 20), so the waves of one workgroup
+    take different variants and meet at the same barriers; a second case scales a range of rows of all heads, which
+    sends whole workgroups one way or the other."""
+    cfg = synth.KsaConfig("mixed_reference", 1, 8, 2, 128, 2048, 64, 8, 1, seed=909090)
+    q, k, v = synth.make_prefill_inputs(cfg)
+    for what in ("one head of each group", "the second half of the rows"):
+        qs = q.clone()
+        if what.startswith("one head"):
+            qs[:, :, 1::4] = qs[:, :, 1::4] * 4            # exact in bf16
+        else:
+            qs[:, cfg.aug_len // 2:] = qs[:, cfg.aug_len // 2:] * 4
+        o_gpu, lse_gpu = gpu_prefill(cfg, qs, k, v)
+        o_ref, lse_ref = O.prefill(qs.float().numpy(), k.float().numpy(), v.float().numpy(), cfg.n_text, cfg.chunk_len,
+                                   cfg.n_summary, cfg.window_chunks)
+        check(o_gpu, lse_gpu, o_ref, lse_ref, f"mixed reference, {what} x 4")
+
+
 SMALL = [
     # name, B, Hq, Hkv, d, n, c, m, C
     ("ragged_q_tiles", 2, 4, 2, 128, 576, 64, 8, 1),      # n not a multiple of the query tile
