@@ -312,6 +312,133 @@ def test_bench_shape_128k_sampled_rows():
     sampled_compare(cfg, q_rows, sorted(set(k_rows)), cfg.name)
 
 
+def uniform_weight_gradients(cfg, q, v, g, kv_head, key_rows):
+    """dK and dV of the listed augmented key rows of one KV head (batch 0) when every key is ZERO: all scores are 0, a
+    row's weights are 1 / count_i on its visible keys, and everything has a closed form that costs O(L d) per key:
+      O_i = mean of the visible v,  delta_i = dO_i . O_i,  dS_ij = (dO_i . v_j - delta_i) / count_i,
+      dV_j = sum_i [i sees j] dO_i / count_i,  dK_j = scale sum_i [i sees j] dS_ij q_i     (summed over the group's heads).
+    Returns (dK, root of the sum of its squared terms), the same for dV, and the counts.  Visible sets and counts are
+    written out from Eq. 3 here (prefix sums over the two index spaces); the caller checks a sample of them against
+    the oracle's mask rows."""
+    c, m, C = cfg.chunk_len, cfg.n_summary, cfg.window_chunks
+    n, J, d = cfg.n_text, cfg.n_text // cfg.chunk_len, cfg.head_dim
+    w = c + m
+    grp = cfg.n_q_heads // cfg.n_kv_heads
+    scale = 1.0 / np.sqrt(d)
+    aug_t = np.arange(n) // c * w + np.arange(n) % c                   # augmented row of text index
+    aug_s = np.arange(J * m) // m * w + c + np.arange(J * m) % m       # ... of summary ordinal
+    vv = v[0, :, kv_head].astype(np.float64)
+    pt = np.concatenate([np.zeros((1, d)), np.cumsum(vv[aug_t], axis=0)])     # prefix sums over text indices
+    ps = np.concatenate([np.zeros((1, d)), np.cumsum(vv[aug_s], axis=0)])     # ... over summary ordinals
+    ti = np.arange(n)
+    first = np.maximum(ti // c - C, 0)                                 # first chunk of the window of text row ti
+    cnt_t = (ti - first * c + 1) + first * m
+    o_t = (pt[ti + 1] - pt[first * c] + ps[first * m]) / cnt_t[:, None]
+    u = np.arange(J * m)
+    cnt_s = c + u % m + 1
+    o_s = (pt[(u // m + 1) * c] - pt[(u // m) * c] + ps[u + 1] - ps[u // m * m]) / cnt_s[:, None]
+    out_k, out_v = [], []
+    for row in key_rows:
+        jc, r = row // w, row % w
+        if r < c:      # text key: seen by the text rows from itself to the end of chunk jc + C, and by its chunk's summaries
+            tsel = np.arange(jc * c + r, min(n, (jc + C + 1) * c))
+            ssel = np.arange(jc * m, (jc + 1) * m)
+        else:          # summary key: seen by the text rows behind its window and by the later summaries of its chunk
+            tsel = np.arange(min(n, (jc + C + 1) * c), n)
+            ssel = np.arange(jc * m + (r - c), (jc + 1) * m)
+        dk, dv, sq_k, sq_v = np.zeros(d), np.zeros(d), np.zeros(d), np.zeros(d)
+        for h in range(kv_head * grp, (kv_head + 1) * grp):
+            for sel, aug, cnt, o in ((tsel, aug_t, cnt_t, o_t), (ssel, aug_s, cnt_s, o_s)):
+                if len(sel) == 0:
+                    continue
+                gh = g[0, aug[sel], h].astype(np.float64)
+                qh = q[0, aug[sel], h].astype(np.float64)
+                tv = gh / cnt[sel, None]
+                ds = (gh @ vv[row] - (gh * o[sel]).sum(axis=1)) / cnt[sel]
+                tk = scale * ds[:, None] * qh
+                dv += tv.sum(axis=0)
+                dk += tk.sum(axis=0)
+                sq_v += (tv ** 2).sum(axis=0)
+                sq_k += (tk ** 2).sum(axis=0)
+        out_k.append((dk, np.sqrt(sq_k)))
+        out_v.append((dv, np.sqrt(sq_v)))
+    unzip = lambda xs: (np.array([x[0] for x in xs]), np.array([x[1] for x in xs]))
+    return unzip(out_k), unzip(out_v), (aug_t, cnt_t, aug_s, cnt_s)
+
+
+def test_bench_shape_128k_early_summary_keys_closed_form():
+    """The summary keys of the FIRST chunks at the benchmark's configuration and launch: each is read by every text row
+    behind its window (131 000 rows x 4 query heads: the dK/dV kernel's longest accumulation, 96 % of its work), which
+    the oracle cannot recompute in reasonable time.  With all keys zero the weights are uniform and dK, dV of single
+    keys have a closed form (uniform_weight_gradients); the forward call of the same run must return log(count) as
+    its log-sum-exp.  Per-entry bar: every term of the sum passes through one bf16 rounding (P for dV, dS for dK:
+    relative 2^-9, independent from term to term), so the sum is off by about 2^-9 times the root of the sum of the
+    squared terms, which the closed form provides: six times that, plus the rounding of the bf16 result (2^-8 of the
+    entry) -- 2e-3 to 6e-3 here, well inside the general 2e-2.  Two text keys ride along."""
+    cfg = synth.CONFIGS["prefill_128k"]
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    k = torch.zeros_like(k)
+    lay = K.ksa_build_layout(params_of(cfg))
+    qd, kd, vd, gd = q.cuda(), k.cuda(), v.cuda(), g.cuda()
+    o, lse = K.ksa_prefill_fwd(lay, qd, kd, vd)
+    dq, dk, dv = K.ksa_prefill_bwd(lay, qd, kd, vd, o, lse, gd)
+    torch.cuda.synchronize()
+    c, m, w = cfg.chunk_len, cfg.n_summary, cfg.chunk_len + cfg.n_summary
+    n_sum = cfg.n_text // c * m
+    key_rows = [aug_summary(cfg, 0), aug_summary(cfg, 5), aug_summary(cfg, 1000), aug_summary(cfg, n_sum // 2),
+                aug_text(cfg, 7), aug_text(cfg, 70000)]
+    qn, vn, gn = (x.float().numpy() for x in (q, v, g))
+    for kv_head in (0, cfg.n_kv_heads - 1):
+        (rk, sk), (rv, sv), (aug_t, cnt_t, aug_s, cnt_s) = uniform_weight_gradients(cfg, qn, vn, gn, kv_head, key_rows)
+        got_k = dk[0, key_rows, kv_head].float().cpu().numpy()
+        got_v = dv[0, key_rows, kv_head].float().cpu().numpy()
+        for name, got, ref, sq in (("dk", got_k, rk, sk), ("dv", got_v, rv, sv)):
+            err = np.abs(got - ref)
+            bar = 1e-4 + 6 * 2.0 ** -9 * sq + REL * np.abs(ref)
+            say(f"  uniform weights, KV head {kv_head} {name}: max-abs {err.max():.3e} (largest entry {np.abs(ref).max():.3f}, "
+                f"bars {bar.min():.2e} .. {bar.max():.2e}, largest error / bar {np.max(err / bar):.2f})")
+            assert (err <= bar).all(), name
+    # the counts behind the closed form against the oracle's mask rows (a sample), and the forward's log-sum-exp
+    # against log(count) for every row of one head
+    rng = np.random.default_rng(77)
+    for ti in [0, 63, 64, 129] + [int(x) for x in rng.integers(0, cfg.n_text, 4)]:
+        assert O.mask_row(int(aug_t[ti]), cfg.n_text, c, m, cfg.window_chunks).sum() == cnt_t[ti]
+    for u in [0, 7, 8] + [int(x) for x in rng.integers(0, n_sum, 3)]:
+        assert O.mask_row(int(aug_s[u]), cfg.n_text, c, m, cfg.window_chunks).sum() == cnt_s[u]
+    want_lse = np.empty(cfg.aug_len)
+    want_lse[aug_t], want_lse[aug_s] = np.log(cnt_t), np.log(cnt_s)
+    lerr = np.abs(lse[0, 3].double().cpu().numpy() - want_lse)
+    say(f"  uniform weights: lse max-abs error {lerr.max():.3e}")
+    assert lerr.max() <= 4e-3
+
+
+def test_bench_shape_128k_conservation():
+    """Two identities that involve every key of the 128K workload at once (N(0,1) inputs, the benchmark's launch): the
+    rows of dS sum to zero, so sum_j dK_j = scale sum_i (sum_j dS_ij) q_i = 0; the rows of P sum to one, so
+    sum_j dV_j = sum_i dO_i (per KV head, over the group's query heads).  Each output is rounded to bf16 (relative
+    2^-9, independent), so a sum over L entries is off by about 2^-9 sqrt(sum of squares); the bars are six times
+    that plus the same for the fp32 accumulation of the weights' rounding."""
+    cfg = synth.CONFIGS["prefill_128k"]
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    lay = K.ksa_build_layout(params_of(cfg))
+    qd, kd, vd, gd = q.cuda(), k.cuda(), v.cuda(), g.cuda()
+    o, lse = K.ksa_prefill_fwd(lay, qd, kd, vd)
+    dq, dk, dv = K.ksa_prefill_bwd(lay, qd, kd, vd, o, lse, gd)
+    torch.cuda.synchronize()
+    grp = cfg.n_q_heads // cfg.n_kv_heads
+    sum_dk = dk.double().sum(dim=1)[0].cpu().numpy()                                   # [Hkv, d]
+    sum_dv = dv.double().sum(dim=1)[0].cpu().numpy()
+    sum_g = gd.double().sum(dim=1)[0].view(cfg.n_kv_heads, grp, cfg.head_dim).sum(dim=1).cpu().numpy()
+    bar_k = 12 * 2.0 ** -9 * np.sqrt((dk.double() ** 2).sum(dim=1)[0].cpu().numpy())
+    bar_v = 12 * 2.0 ** -9 * np.sqrt((dv.double() ** 2).sum(dim=1)[0].cpu().numpy())
+    say(f"  conservation: |sum dK| max {np.abs(sum_dk).max():.3e} (bar {bar_k.min():.3e}), "
+        f"|sum dV - sum dO| max {np.abs(sum_dv - sum_g).max():.3e} (bar {bar_v.min():.3e}, sums up to {np.abs(sum_g).max():.1f})")
+    assert (np.abs(sum_dk) <= bar_k).all()
+    assert (np.abs(sum_dv - sum_g) <= bar_v).all()
+
+
 def test_prefill_4k_sampled_rows():
     """The 4K workload (two sequences, 32 query / 8 KV heads): random query rows and key rows of both kinds."""
     cfg = synth.CONFIGS["prefill_4k"]
