@@ -313,8 +313,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dq_kernel(const BwdArgs a) {
     rq.k_base = kbase, rq.v_base = vbase, rq.seg = 0, rq.first = 0, rq.full = false;
 #pragma unroll
     for (int i = 0; i < NI; ++i) rq.off[i] = 0;
+    // Both shift counts in one scalar register, byte `sp` that of index space sp (a shift takes its count modulo 32).
+    // Opaque to the compiler: a select between two kernel arguments is otherwise compiled into a scalar load of the
+    // selected argument inside the tile loop, and the wait for it drains every LDS operand read in flight.
+    unsigned shifts = ((unsigned)a.c_shift & 31u) | (((unsigned)a.m_shift & 31u) << 8);
+    asm volatile("" : "+s"(shifts));
     auto chunk_of = [&](int sp, int idx) {
-        if constexpr (POW2) return idx >> (sp == KSA_SPACE_TEXT ? a.c_shift : a.m_shift);
+        if constexpr (POW2) return idx >> (shifts >> (sp * 8));
         return idx / (sp == KSA_SPACE_TEXT ? a.c : a.m);
     };
     auto prepare_tile = [&]() {   // scalar part
@@ -717,8 +722,13 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) rq.q_off[i] = rq.g_off[i] = 0;
     // compact index -> chunk number and augmented row, in index space sp (scalar sp)
+    // Both shift counts in one scalar register, byte `sp` that of index space sp (a shift takes its count modulo 32).
+    // Opaque to the compiler: a select between two kernel arguments is otherwise compiled into a scalar load of the
+    // selected argument inside the tile loop, and the wait for it drains every LDS operand read in flight.
+    unsigned shifts = ((unsigned)a.c_shift & 31u) | (((unsigned)a.m_shift & 31u) << 8);
+    asm volatile("" : "+s"(shifts));
     auto chunk_of = [&](int sp, int idx) {
-        if constexpr (POW2) return idx >> (sp == KSA_SPACE_TEXT ? a.c_shift : a.m_shift);
+        if constexpr (POW2) return idx >> (shifts >> (sp * 8));
         return idx / (sp == KSA_SPACE_TEXT ? a.c : a.m);
     };
     auto prepare_tile = [&]() {   // scalar part
@@ -824,8 +834,10 @@ __global__ __launch_bounds__(NW * 64) void ksa_bwd_dkv_kernel(const BwdArgs a) {
     // stretches.
     auto step = [&](auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        // the tile in work is complete when at most the loads of the two younger ones are outstanding
-        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LOADS_PER_TILE) & 15) | (((2 * LOADS_PER_TILE) >> 4) << 14));
+        // the tile in work is complete when at most the loads of the STAGES - 2 younger ones are outstanding
+        constexpr int YOUNGER = (STAGES - 2) * LOADS_PER_TILE;
+        static_assert(YOUNGER < 64, "vmcnt is a six-bit count");
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (YOUNGER & 15) | ((YOUNGER >> 4) << 14));
         __syncthreads();   // that tile is published; everybody is done with the stage the next request overwrites
         const int q_rows = buf * 2 * BYTES + ll.rows, g_rows = q_rows + BYTES;
         const int q_cols = buf * 2 * BYTES + ll.cols, g_cols = q_cols + BYTES;
