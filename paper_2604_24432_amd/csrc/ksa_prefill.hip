@@ -770,9 +770,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     // row maximum (TRACK below: row maxima of every block, a raise of the reference with a rescale of the accumulators
     // when a block exceeds it).  Where it is provably safe the pipelined kernel fixes the reference up front instead:
     // |s_ij| = |q_i . k_j| <= |q_i| max_j |k_j| =: B_i (Cauchy-Schwarz; the largest K row norm of the KV head comes from
-    // the preparation pass), so with m_i = B_i - 64 / (scale log2 e) every exponent (s_ij - m_i) scale log2 e is at
-    // most 64, and at least 64 - 2 B_i scale log2 e.  If B_i scale log2 e <= 60 for every row of the wave, the exponents
-    // lie in [-56, 64]: no overflow, no underflow, whatever the data -- and no row maxima, no raise decision and no
+    // the preparation pass), so with m_i = B_i - 32 / (scale log2 e) every exponent (s_ij - m_i) scale log2 e is at
+    // most 32, and at least 32 - 2 B_i scale log2 e.  If B_i scale log2 e <= 60 for every row of the wave, the exponents
+    // lie in [-88, 32]: every weight is a normal number in bf16 and fp32, whatever the data, the fp32 sums of p and of
+    // p v stay finite unless |v| times the number of keys exceeds 2^95 (2^119 with the running maximum), and a product
+    // p v can only be lost to underflow where |v| < 2^-38 -- and there are no row maxima, no raise decision and no
     // rescale in the loop (3 - 4 % of the time of the 128K workload).  The result is the same softmax: the reference
     // cancels in O = sum(p v) / sum(p) and is added back in the log-sum-exp.  Waves whose bound is larger (keys or
     // queries of unusual size) or not a number take the tracking variant; both variants execute the same barriers,
@@ -792,7 +794,7 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             n2 += other_half(n2);                                        // the lane pair of a row holds its two halves
             const float bound = __builtin_sqrtf(n2 * kmax2) * 1.002f;    // raw score units; the factor covers fp32 rounding
             ok &= bound * a.scale_log2e <= 60.f;                         // false for NaN
-            m_static[qb] = bound - 64.f / a.scale_log2e;
+            m_static[qb] = bound - 32.f / a.scale_log2e;
         }
         static_ok = __builtin_amdgcn_ballot_w64(!ok) == 0;
     } else {

@@ -127,6 +127,22 @@ def test_fixed_and_running_reference_side_by_side():
         check(o_gpu, lse_gpu, o_ref, lse_ref, f"mixed reference, {what} x 4")
 
 
+@pytest.mark.parametrize("log2_v", [70, -30])
+def test_values_of_extreme_magnitude(log2_v):
+    """With the fixed reference the weights reach 2^32 (not 1, as with a running maximum), so the sums of p v are larger
+    by that factor: V rows of size 2^70 (times up to 4 160 visible keys times 2^32: 2^114 < 2^127) must still give
+    finite outputs, and V rows of size 2^-30 must not be lost to underflow (the smallest weight is 2^-88, the
+    smallest product about 2^-120).  The scaling is exact in bf16, so the oracle's output of the unscaled problem times
+    the factor is the expected result."""
+    cfg = synth.KsaConfig("extreme_values", 1, 8, 2, 128, 4096, 64, 8, 1, seed=515151)
+    q, k, v = synth.make_prefill_inputs(cfg)
+    f = 2.0 ** log2_v
+    o_gpu, lse_gpu = gpu_prefill(cfg, q, k, v * f)
+    o_ref, lse_ref = O.prefill(q.float().numpy(), k.float().numpy(), v.float().numpy(), cfg.n_text, cfg.chunk_len,
+                               cfg.n_summary, cfg.window_chunks)
+    check((o_gpu.astype(np.float64) / f).astype(np.float32), lse_gpu, o_ref, lse_ref, f"V x 2^{log2_v}")
+
+
 SMALL = [
     # name, B, Hq, Hkv, d, n, c, m, C
     ("ragged_q_tiles", 2, 4, 2, 128, 576, 64, 8, 1),      # n not a multiple of the query tile
