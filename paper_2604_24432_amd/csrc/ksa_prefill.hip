@@ -1095,8 +1095,17 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     *reinterpret_cast<u32x4 *>(a.o + b * a.os[0] + (int64_t)aug_row(a, q_space, row0 + row) * a.os[1] +
                                                hq * a.os[2] + piece * 8) = x;
             }
-            if (a.lse && h == 0 && q_valid[qb])
-                a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] = st.m_ref[qb] * a.scale + __logf(l_row);
+            if (a.lse && h == 0 && q_valid[qb]) {
+                // log-sum-exp = (m_ref scale log2 e + log2 l) ln 2 with l = f 2^e split first.  With the fixed reference
+                // the two terms are large and of opposite sign (a row of 10^5 keys: -12 and +29 in the exponent
+                // domain, Q = 0: -32 and +49), and adding them as they are would cost two or three bits; m_ref scale
+                // log2 e is the rounded product the weights were computed with.
+                float msl = st.m_ref[qb] * sl;
+                asm volatile("" : "+v"(msl));   // (not contracted with the sum below)
+                const float t = msl + (float)__builtin_amdgcn_frexp_expf(l_row);
+                a.lse[((int64_t)b * a.n_q_heads + hq) * a.aug_len + q_aug[qb]] =
+                    fmaf(t, 0.6931471805599453f, __logf(__builtin_amdgcn_frexp_mantf(l_row)));
+            }
         }
     }
     };

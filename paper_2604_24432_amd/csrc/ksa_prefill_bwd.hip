@@ -150,10 +150,6 @@ __device__ __forceinline__ void mfma_score(f32x16 &acc, const bf16x8 &a_op, cons
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a_op), "a"(b_resident));
 }
 
-// 24 wait states: more than the 16 passes of the last mfma_score() plus the margin the ISA asks for before a VALU
-// instruction may read an MFMA result.
-__device__ __forceinline__ void scores_settle() { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); }
-
 // The last mfma_acc() results reach the register file (16 passes of 4 cycles) before anything reads them.
 __device__ __forceinline__ void accumulators_settle() {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");

@@ -130,7 +130,7 @@ def test_fixed_and_running_reference_side_by_side():
 @pytest.mark.parametrize("log2_v", [70, -30])
 def test_values_of_extreme_magnitude(log2_v):
     """With the fixed reference the weights reach 2^32 (not 1, as with a running maximum), so the sums of p v are larger
-    by that factor: V rows of size 2^70 (times up to 4 160 visible keys times 2^32: 2^114 < 2^127) must still give
+    by that factor: V rows of size 2^70 (times up to 624 visible keys times 2^32: about 2^112 < 2^127) must still give
     finite outputs, and V rows of size 2^-30 must not be lost to underflow (the smallest weight is 2^-88, the
     smallest product about 2^-120).  The scaling is exact in bf16, so the oracle's output of the unscaled problem times
     the factor is the expected result."""
@@ -344,6 +344,44 @@ def test_row_counts_of_the_kernel_mask_at_128k(name, c, m, C):
     _, lse = K.ksa_prefill_fwd(lay, q, k, v)
     torch.cuda.synchronize()
     counts = np.rint(np.exp(lse.cpu().numpy().astype(np.float64)))[0]     # [Hq, L]
+    want = closed_form_row_counts(cfg)
+    bad = np.argwhere(counts != want[None, :])
+    assert bad.size == 0, f"{len(bad)} rows differ, first (head, row) {bad[0]}: {counts[tuple(bad[0])]} vs {want[bad[0][1]]}"
+
+
+def as_leading_heads(x, alloc_heads):
+    """x [B, L, H, d] on the host -> the same values on the GPU as heads 0 .. H-1 of a [B, L, alloc_heads, d] tensor
+    (row stride alloc_heads * d elements; the other heads are never read)."""
+    big = torch.empty((x.shape[0], x.shape[1], alloc_heads, x.shape[3]), dtype=x.dtype, device="cuda")
+    view = big[:, :, :x.shape[2]]
+    view.copy_(x)
+    return view
+
+
+def test_one_million_tokens_rows_beyond_4_gib():
+    """n = 2^20 text tokens (1 179 648 augmented rows) at the row strides of the benchmark's head counts (32 query heads:
+    8 KiB per row of q and o; K / V at 4 KiB per row), of which one KV group (4 query heads, 1 KV head) is computed:
+    the rows of the second half lie more than 4 GiB (K / V: more than 2 GiB) behind the tensors' bases, so every
+    address the kernels form has to be 64-bit.  Sampled rows against the oracle, then the mask probe over every row."""
+    cfg = synth.KsaConfig("prefill_1m", 1, 4, 1, 128, 1 << 20, 64, 8, 1, seed=777)
+    say(f"prefill parity (sampled rows) {cfg.name}: L {cfg.aug_len}")
+    q, k, v = synth.make_prefill_inputs(cfg)
+    qd, kd, vd = as_leading_heads(q, 32), as_leading_heads(k, 16), as_leading_heads(v, 16)
+    od = torch.empty((1, cfg.aug_len, 32, cfg.head_dim), dtype=torch.bfloat16, device="cuda")[:, :, :cfg.n_q_heads]
+    assert qd.stride(1) * 2 * (cfg.aug_len - 1) > 1 << 32 and kd.stride(1) * 2 * (cfg.aug_len - 1) > 1 << 32
+    lay = K.ksa_build_layout(params_of(cfg))
+    _, lse = K.ksa_prefill_fwd(lay, qd, kd, vd, o=od)
+    torch.cuda.synchronize()
+    rows = synth.sample_rows(cfg, 256).numpy()
+    o_ref, lse_ref = O.prefill(q.float().numpy(), k.float().numpy(), v.float().numpy(), cfg.n_text, cfg.chunk_len,
+                               cfg.n_summary, cfg.window_chunks, rows=rows)
+    rows_d = torch.from_numpy(rows).cuda()
+    check(od[:, rows_d].float().cpu().numpy(), lse[:, :, rows_d].cpu().numpy(), o_ref, lse_ref, cfg.name)
+    assert bool(torch.isfinite(od.float()).all()) and bool(torch.isfinite(lse).all())
+    qd.zero_()
+    _, lse = K.ksa_prefill_fwd(lay, qd, kd, vd, o=od)
+    torch.cuda.synchronize()
+    counts = np.rint(np.exp(lse.cpu().numpy().astype(np.float64)))[0]
     want = closed_form_row_counts(cfg)
     bad = np.argwhere(counts != want[None, :])
     assert bad.size == 0, f"{len(bad)} rows differ, first (head, row) {bad[0]}: {counts[tuple(bad[0])]} vs {want[bad[0][1]]}"

@@ -312,6 +312,50 @@ def test_bench_shape_128k_sampled_rows():
     sampled_compare(cfg, q_rows, sorted(set(k_rows)), cfg.name)
 
 
+def as_leading_heads(x, alloc_heads):
+    """x [B, L, H, d] on the host -> the same values on the GPU as heads 0 .. H-1 of a [B, L, alloc_heads, d] tensor."""
+    big = torch.empty((x.shape[0], x.shape[1], alloc_heads, x.shape[3]), dtype=x.dtype, device="cuda")
+    view = big[:, :, :x.shape[2]]
+    view.copy_(x)
+    return view
+
+
+def test_one_million_tokens_rows_beyond_4_gib():
+    """n = 2^20 text tokens at the row strides of the benchmark's head counts (q, o, d_o, dq: 8 KiB per row; k, v, dk,
+    dv: 4 KiB per row), one KV group computed: the rows of the second half lie more than 4 GiB behind the tensors'
+    bases.  Random query rows; text keys anywhere, summary keys of the last chunks (the early ones would cost the oracle
+    hours)."""
+    cfg = synth.KsaConfig("backward_1m", 1, 4, 1, 128, 1 << 20, 64, 8, 1, seed=778)
+    q, k, v = synth.make_prefill_inputs(cfg)
+    g = synth.make_upstream_gradient(cfg)
+    lay = K.ksa_build_layout(params_of(cfg))
+    qd, gd = as_leading_heads(q, 32), as_leading_heads(g, 32)
+    kd, vd = as_leading_heads(k, 16), as_leading_heads(v, 16)
+    empty = lambda heads, used: torch.empty((1, cfg.aug_len, heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")[:, :, :used]
+    od, dqd = empty(32, cfg.n_q_heads), empty(32, cfg.n_q_heads)
+    dkd, dvd = empty(16, cfg.n_kv_heads), empty(16, cfg.n_kv_heads)
+    _, lse = K.ksa_prefill_fwd(lay, qd, kd, vd, o=od)
+    K.ksa_prefill_bwd(lay, qd, kd, vd, od, lse, gd, dq=dqd, dk=dkd, dv=dvd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4200)
+    n, n_sum = cfg.n_text, (cfg.n_text // cfg.chunk_len) * cfg.n_summary
+    q_rows = sorted(set([0, cfg.aug_len - 1] + [int(x) for x in rng.integers(0, cfg.aug_len, 6)]
+                        + [int(x) for x in rng.integers(cfg.aug_len // 2, cfg.aug_len, 6)]))
+    k_rows = [aug_text(cfg, int(x)) for x in rng.integers(0, n, 2)] + [aug_text(cfg, int(x)) for x in rng.integers(n // 2, n, 2)] + \
+             [aug_text(cfg, n - 1)] + [aug_summary(cfg, n_sum - 1 - int(x)) for x in rng.integers(0, 4 * cfg.n_summary, 2)] + \
+             [aug_summary(cfg, n_sum - 3 * cfg.n_summary)]
+    k_rows = sorted(set(k_rows))
+    say(f"backward parity (sampled rows) {cfg.name}: {len(q_rows)} query rows, {len(k_rows)} key rows")
+    rq, rk, rv = O.prefill_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.float().numpy(), cfg.n_text,
+                               cfg.chunk_len, cfg.n_summary, cfg.window_chunks, q_rows=q_rows, k_rows=k_rows)
+    qr, kr = torch.tensor(q_rows, device="cuda"), torch.tensor(k_rows, device="cuda")
+    check(dqd[:, qr].float().cpu().numpy(), rq, cfg.name + " dq")
+    check(dkd[:, kr].float().cpu().numpy(), rk, cfg.name + " dk")
+    check(dvd[:, kr].float().cpu().numpy(), rv, cfg.name + " dv")
+    for t in (dqd, dkd, dvd):
+        assert bool(torch.isfinite(t.float()).all())
+
+
 def uniform_weight_gradients(cfg, q, v, g, kv_head, key_rows):
     """dK and dV of the listed augmented key rows of one KV head (batch 0) when every key is ZERO: all scores are 0, a
     row's weights are 1 / count_i on its visible keys, and everything has a closed form that costs O(L d) per key:
