@@ -108,12 +108,10 @@ def test_decode_out_of_range_position_gives_nan_and_reads_nothing():
     assert torch.isfinite(o[0]).all() and torch.isnan(o[1]).all() and torch.isnan(lse[1]).all()
 
 
-def test_decode_128k_context_full_compare():
-    """The benchmark workload: batch 64, 32/8 heads, d 128, position 131072+63 (16376 visible summaries +
-    128 text rows per KV head), in the launch configuration bench.py times (default split count)."""
-    cfg = synth.CONFIGS["decode_128k"]
+def long_context_compare(cfg, pos, slabs):
+    """One decode step of every sequence of cfg at text position pos, in the default launch configuration; the
+    sequences of `slabs` (ranges of eight) are compared with the oracle."""
     c, m, C = cfg.chunk_len, cfg.n_summary, cfg.window_chunks
-    pos = cfg.decode_pos
     n_cap = (pos // c + 1) * c
     say(f"decode parity {cfg.name}: pos {pos} capacity {n_cap}")
     p = K.make_params(cfg.batch, n_cap, c, m, C, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
@@ -125,9 +123,10 @@ def test_decode_128k_context_full_compare():
     pos_t = torch.full((cfg.batch,), pos, dtype=torch.int32, device="cuda")
     o, lse = K.ksa_decode_fwd(p, q, k_cache, v_cache, pos_t)
     torch.cuda.synchronize()
+    assert bool(torch.isfinite(o.float()).all()) and bool(torch.isfinite(lse).all())
     o_gpu, lse_gpu = o.float().cpu().numpy(), lse.cpu().numpy()
     errs, lerrs = [], []
-    for b0 in range(0, cfg.batch, 8):      # the oracle takes fp32 copies: go eight sequences at a time
+    for b0 in slabs:      # the oracle takes fp32 copies: go eight sequences at a time
         sl = slice(b0, b0 + 8)
         o_ref, lse_ref = O.decode(q[sl].float().cpu().numpy(), k_sum[sl].float().cpu().numpy(),
                                   v_sum[sl].float().cpu().numpy(), k_txt[sl].float().cpu().numpy(),
@@ -138,3 +137,20 @@ def test_decode_128k_context_full_compare():
     err, lerr = np.concatenate(errs), np.concatenate(lerrs)
     say(f"  max-abs {err.max():.3e} mean-abs {err.mean():.3e} lse max-abs {lerr.max():.3e}")
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS and lerr.max() <= LSE_ABS
+    return k_cache
+
+
+def test_decode_128k_context_full_compare():
+    """The benchmark workload: batch 64, 32/8 heads, d 128, position 131072+63 (16376 visible summaries +
+    128 text rows per KV head), in the launch configuration bench.py times (default split count)."""
+    cfg = synth.CONFIGS["decode_128k"]
+    long_context_compare(cfg, cfg.decode_pos, range(0, cfg.batch, 8))
+
+
+def test_decode_1m_context_cache_beyond_4_gib():
+    """Position 2^20 + 63: 131 064 visible summaries + 128 text rows per KV head; 72 sequences of 8/2 heads make each
+    cache 4.8 GB, so the last sequences lie more than 4 GiB behind the cache's base.  First and last eight sequences
+    against the oracle."""
+    cfg = synth.KsaConfig("decode_1m", 72, 8, 2, 128, (1 << 20) + 64, 64, 8, 1, seed=4242)
+    k_cache = long_context_compare(cfg, (1 << 20) + 63, [0, cfg.batch - 8])
+    assert k_cache.stride(0) * 2 * (cfg.batch - 8) > 1 << 32
