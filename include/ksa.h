@@ -148,6 +148,8 @@ size_t ksa_prefill_workspace_bytes(const ksa_layout *layout);
  *   stream-ordered.
  *   stream: hipStream_t (NULL = default stream).
  * The main kernel walks the layout's schedule: bf16 MFMA for Q K^T and P V, fp32 online softmax.
+ * Value range: the weights of a row are kept within [2^-88, 2^32] relative to its reference and summed in fp32, so
+ * the output is finite as long as max |v| times the number of visible keys stays below 2^95.
  * Errors: INVALID_ARG (null tensors or workspace, misaligned pointers: 16-byte alignment required),
  * WORKSPACE_TOO_SMALL, HIP.
  */
