@@ -765,6 +765,35 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
     wlo_t = __builtin_amdgcn_readfirstlane(wlo_t), whi_t = __builtin_amdgcn_readfirstlane(whi_t);
     wlo_s = __builtin_amdgcn_readfirstlane(wlo_s), whi_s = __builtin_amdgcn_readfirstlane(whi_s);
 
+    const __bf16 *kbase = a.k + b * a.ks[0] + hkv * a.ks[2];
+    const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
+    // ---- the first key tiles of the first run are requested right behind the Q rows ----------------------
+    // A workgroup owns its compute unit alone (LDS, registers), so nothing hides its start-up: the Q rows come from
+    // HBM (about 4 us on the loaded chip), and the first two key tiles another 2 us if they were only requested once
+    // the Q rows are there.  Requested here they travel together.  Nothing else touches the LDS ring before the run's
+    // own set-up in the loop below, which repeats this arithmetic and skips the requests.
+    if constexpr (PIPELINED) {
+        const int space = run_space[0], seg_begin = run_begin[0], seg_end = run_end[0];
+        const int second = seg_end - seg_begin > BN ? 1 : 0;
+        LaneOffsets<D> off;
+        lane_offsets<D>(a, space, seg_begin, 0x7fffffff, wave, lane, aug_row(a, space, seg_begin), off);
+        const int vt_stride = space == KSA_SPACE_TEXT ? a.nt_pad : a.ns_pad;
+        lane_offsets_vt<D>(vt_stride, wave, lane, off);
+        const __bf16 *vtbase = a.vt + (space == KSA_SPACE_TEXT ? 0 : a.vt_sum_off) +
+                               ((int64_t)(b * a.n_kv_heads + hkv) * D) * vt_stride + seg_begin;
+        const unsigned lds0 = (unsigned)(size_t)lds;
+        const unsigned k_wave = lds0 + K0 + RW * wave * (D * 2), v_wave = lds0 + V0 + T::VROWS * wave * 128;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int tt = t == 0 ? 0 : second;
+            const __bf16 *kg = kbase + (int64_t)aug_row(a, space, seg_begin + tt * BN) * a.ks[1], *vg = vtbase + tt * BN;
+#pragma unroll
+            for (int i = 0; i < T::NI; ++i) issue_tile_load_part<D>(kg, (unsigned)off.k[i] * 2u, k_wave + t * T::BYTES, i);
+#pragma unroll
+            for (int i = 0; i < T::NIV; ++i) issue_vt_load_part<D>(vg, (unsigned)off.vt[i] * 2u, v_wave + t * T::BYTES, i);
+        }
+    }
+
     // ---- the reference of the softmax -----------------------------------------------------------------
     // Online softmax needs a reference m_i per row with s_ij - m_i bounded above.  The usual choice is the running
     // row maximum (TRACK below: row maxima of every block, a raise of the reference with a rescale of the accumulators
@@ -820,8 +849,6 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             for (int g = 0; g < 16; ++g) oacc[qb][db][g] = 0.f;
     }
 
-    const __bf16 *kbase = a.k + b * a.ks[0] + hkv * a.ks[2];
-    const __bf16 *vbase = a.v + b * a.ks[0] + hkv * a.ks[2];
     // the A operand of sum_half(); opaque from here on: a value the compiler can see through would be re-materialised by
     // VALU moves right in front of the raw MFMAs that read it, and the compiler inserts no wait states for those
     const unsigned ind1 = (lane == 0 || lane == 32 || lane == 17 || lane == 49) ? 0x3f803f80u : 0u;
@@ -894,9 +921,11 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
             // scores.  (One loop with the choice made per tile costs register copies at every join of the two variants.)
             {
                 const int second = n_tiles > 1 ? 1 : 0;
-                __syncthreads();                     // earlier readers of the LDS buffers are done
-                issue_tile(0, 0);
-                issue_tile(second, T::BYTES);
+                if (seg > 0) {                       // (the first run's tiles were requested together with the Q rows)
+                    __syncthreads();                 // earlier readers of the LDS buffers are done
+                    issue_tile(0, 0);
+                    issue_tile(second, T::BYTES);
+                }
                 __builtin_amdgcn_s_waitcnt(0);
                 __syncthreads();
                 f32x16 sv_a[QB], sv_b[QB];
