@@ -1116,13 +1116,23 @@ __global__ __launch_bounds__(NW * 64) void ksa_prefill_kernel(const PrefillArgs 
                     *reinterpret_cast<bf16x4 *>(stg + r * ROWB + (db * 32 + g4 * 8 + h * 4) * 2) = pk;
                 }
             const int row0 = q_begin + (wrow * QB + qb) * 32;
+            // the lane's piece of row 0 of its (batch, head); a row's address is this plus augmented row x row stride.
+            // The pipelined instantiation only sees chunk shapes that are powers of two (the scheduler's condition), so
+            // the row map is two shifts and a multiply-add per store rather than the general map with its divisions
+            // (60 instructions per store, 16 stores per wave, with the matrix pipe idle).
+            const int piece = lane % T::CH;
+            __bf16 *const obase = a.o + b * a.os[0] + hq * a.os[2] + piece * 8;
+            const int e_sh = q_space == KSA_SPACE_TEXT ? a.c_shift : a.m_shift;
+            const int e_msk = (q_space == KSA_SPACE_TEXT ? a.c : a.m) - 1, e_add = q_space == KSA_SPACE_TEXT ? 0 : a.c;
 #pragma unroll
             for (int i = 0; i < 32 / T::RPI; ++i) {
-                const int row = T::RPI * i + lane / T::CH, piece = lane % T::CH;
+                const int row = T::RPI * i + lane / T::CH;
                 const u32x4 x = *reinterpret_cast<const u32x4 *>(stg + row * ROWB + piece * 16);
-                if (row0 + row < q_end)
-                    *reinterpret_cast<u32x4 *>(a.o + b * a.os[0] + (int64_t)aug_row(a, q_space, row0 + row) * a.os[1] +
-                                               hq * a.os[2] + piece * 8) = x;
+                const int idx = row0 + row;
+                if (idx < q_end) {
+                    const int arow = PIPELINED ? (idx >> e_sh) * a.w + (idx & e_msk) + e_add : aug_row(a, q_space, idx);
+                    *reinterpret_cast<u32x4 *>(obase + (int64_t)arow * a.os[1]) = x;
+                }
             }
             if (a.lse && h == 0 && q_valid[qb]) {
                 // log-sum-exp = (m_ref scale log2 e + log2 l) ln 2 with l = f 2^e split first.  With the fixed reference
