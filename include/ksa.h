@@ -83,7 +83,9 @@ void ksa_layout_destroy(ksa_layout *layout);
 
 /*
  * Copies the schedule to the current HIP device (one hipMalloc + one hipMemcpy).  ksa_prefill_fwd
- * does this itself on first use; calling it ahead keeps the first timed call allocation-free.
+ * does this itself on first use; calling it ahead keeps the first timed call allocation-free.  After it,
+ * ksa_prefill_fwd and ksa_prefill_bwd enqueue kernels only (no allocation, memset or synchronisation) and may be
+ * captured into a HIP graph.
  */
 int ksa_layout_upload(ksa_layout *layout);
 
